@@ -1,0 +1,359 @@
+"""CPU oracle for the verification hot path.  TEST INFRASTRUCTURE ONLY.
+
+Nothing in the product path may import this file; it exists so that tests, the smoke check and the
+benchmark's CPU-baseline leg can compare the GPU library against a plain, slow, obviously correct
+implementation.  It shares no code with the GPU library.  Everything is float64 numpy; a matrix
+product is `@`, everything else is written out as the definition states it, with no blocking,
+fusion or reordering.
+
+What it computes, following the paper:
+
+* Section 4 "Full-Sequence Prefill for Parallel Verification", Eq. (1): the verifier runs ONE
+  causal forward pass over the concatenated prompt and output tokens and thereby recovers the
+  hidden state of every position, H' = F_theta(X_prompt || X_output)          -> `prefill`.
+* Section 5.5 "Inference Scheme" (the three-line recurrence S_1 = Embed(x), S_{i+1} = F_i(S_i; W_i),
+  y = Decode(S_{L+1})): the inferencer produces the same states one token at a time and logs
+  them at the segment boundaries                                                -> `decode`.
+* Section 5.7 "Comparison and On-Chain Commitment": Delta = S_hat - S elementwise, a per-token scalar
+  phi(Delta) (mean absolute error is the paper's example), a statistic Psi across tokens (mean),
+  a verdict 1[T_v <= tau]                                                       -> `compare_hidden`,
+  `summary`.
+* Section 5.7, the TokenMatch equation: argmax of the LM head applied to the recomputed last-layer
+  state must reproduce the claimed token                                        -> `token_check`.
+
+The paper never spells out the transformer block F_i; the block here is the Llama-style pre-norm
+block that the evaluation shapes fix (RMSNorm, rotary embedding on half-split pairs, grouped-query
+causal attention scaled by 1/sqrt(head_dim), SwiGLU feed-forward, no biases, untied LM head, final
+RMSNorm).  The "hidden state after layer l" is the residual stream leaving block l, before any
+following norm, for every l including the last.
+
+Readings that go beyond the paper (per-token relative L2 and max-abs instead of one verdict per
+segment; a logit margin for near-tied argmax) are documented where they are implemented.
+
+Pins: every function below is pinned by tests/test_oracle_*.py against closed forms, invariants
+(token-by-token decode equals prefill; causality; batch independence), library routines
+(torch's scaled_dot_product_attention, rms_norm, silu; the `transformers` Llama model on a tiny
+random model) and a scalar-loop brute force.  The values at the full 8B/70B shapes are "parity
+unpinned" by the paper itself (it prints no activations); they rest on the same code being pinned at
+small shapes.
+"""
+from __future__ import annotations
+
+import math
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+# tensor kinds: same numbering as the library's public header (an interface, not shared code)
+EMBED, ATTN_NORM, WQ, WK, WV, WO, FFN_NORM, W_GATE, W_UP, W_DOWN, FINAL_NORM, LM_HEAD = range(12)
+
+WeightFn = Callable[[int, int], np.ndarray]   # (kind, layer0) -> array; matrices are [out, in]
+
+TINY = 1e-30
+
+
+# ------------------------------------------------------------------------------------------------
+# storage formats
+# ------------------------------------------------------------------------------------------------
+
+def upcast(a: np.ndarray) -> np.ndarray:
+    """Exact conversion of a stored tensor to float64 (uint16 arrays hold bf16 bit patterns)."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+# ------------------------------------------------------------------------------------------------
+# building blocks of F_i
+# ------------------------------------------------------------------------------------------------
+
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean(x^2) + eps) * gain, row by row."""
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(gain, dtype=np.float64)
+
+
+def rope_angles(positions: np.ndarray, head_dim: int, base: float) -> np.ndarray:
+    """angle[t, i] = pos_t * base^(-2i/head_dim), i in [0, head_dim/2)."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    inv_freq = np.power(float(base), -2.0 * i / float(head_dim))
+    return np.asarray(positions, dtype=np.float64)[:, None] * inv_freq[None, :]
+
+
+def apply_rope(x: np.ndarray, positions: np.ndarray, base: float) -> np.ndarray:
+    """Rotate the pairs (i, i + head_dim/2) of x [T, heads, head_dim] by the position's angles."""
+    t, h, hd = x.shape
+    half = hd // 2
+    ang = rope_angles(positions, hd, base)
+    c = np.cos(ang)[:, None, :]
+    s = np.sin(ang)[:, None, :]
+    x1 = x[..., :half]
+    x2 = x[..., half:]
+    out = np.empty_like(x, dtype=np.float64)
+    out[..., :half] = x1 * c - x2 * s
+    out[..., half:] = x2 * c + x1 * s
+    return out
+
+
+def softmax_rows(s: np.ndarray) -> np.ndarray:
+    m = np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_positions: np.ndarray) -> np.ndarray:
+    """Grouped-query causal attention for one sequence.
+
+    q [Tq, Hq, hd]; k, v [Tk, Hkv, hd] hold keys/values of positions 0..Tk-1; query row r sits at
+    position q_positions[r] and attends to keys j <= q_positions[r].  Q head j uses KV head
+    j // (Hq / Hkv).  Scores are scaled by 1/sqrt(hd).
+    """
+    tq, hq, hd = q.shape
+    tk, hkv, _ = k.shape
+    group = hq // hkv
+    scale = 1.0 / math.sqrt(hd)
+    out = np.empty((tq, hq, hd), dtype=np.float64)
+    key_pos = np.arange(tk)
+    allowed = key_pos[None, :] <= np.asarray(q_positions)[:, None]          # [Tq, Tk]
+    for j in range(hq):
+        g = j // group
+        s = (q[:, j, :] @ k[:, g, :].T) * scale
+        s = np.where(allowed, s, -np.inf)
+        p = softmax_rows(s)
+        out[:, j, :] = p @ v[:, g, :]
+    return out
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    return x / (1.0 + np.exp(-x))
+
+
+def argmax_lowest(z: np.ndarray) -> np.ndarray:
+    """Row argmax; among equal maxima the lowest index."""
+    return np.argmax(z, axis=-1).astype(np.int64)   # numpy returns the first occurrence
+
+
+# ------------------------------------------------------------------------------------------------
+# the model F_theta
+# ------------------------------------------------------------------------------------------------
+
+class Model:
+    """Shape + weight source.  `weights(kind, layer0)` returns the stored tensor; it is upcast here."""
+
+    def __init__(self, n_layers: int, d_model: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                 d_ffn: int, vocab: int, rms_eps: float, rope_base: float, weights: WeightFn):
+        self.L, self.d, self.hq, self.hkv, self.hd = n_layers, d_model, n_q_heads, n_kv_heads, head_dim
+        self.f, self.v, self.eps, self.base = d_ffn, vocab, float(rms_eps), float(rope_base)
+        self._w = weights
+
+    def w(self, kind: int, layer: int = 0) -> np.ndarray:
+        return upcast(self._w(kind, layer))
+
+
+def _layer_weights(m: Model, l: int) -> Dict[int, np.ndarray]:
+    return {k: m.w(k, l) for k in (ATTN_NORM, WQ, WK, WV, WO, FFN_NORM, W_GATE, W_UP, W_DOWN)}
+
+
+def _block(m: Model, w: Dict[int, np.ndarray], h: np.ndarray, positions: np.ndarray,
+           k_all: Optional[np.ndarray], v_all: Optional[np.ndarray]):
+    """One block F_l on rows h [T, d] at `positions`; k_all/v_all are earlier keys/values (or None).
+
+    Returns (new h, keys, values) with keys/values covering positions 0..max(positions).
+    """
+    t = h.shape[0]
+    u = rmsnorm(h, w[ATTN_NORM], m.eps)
+    q = (u @ w[WQ].T).reshape(t, m.hq, m.hd)
+    k = (u @ w[WK].T).reshape(t, m.hkv, m.hd)
+    v = (u @ w[WV].T).reshape(t, m.hkv, m.hd)
+    q = apply_rope(q, positions, m.base)
+    k = apply_rope(k, positions, m.base)
+    if k_all is not None:
+        k = np.concatenate([k_all, k], axis=0)
+        v = np.concatenate([v_all, v], axis=0)
+    o = causal_attention(q, k, v, positions).reshape(t, m.hq * m.hd)
+    h1 = h + o @ w[WO].T
+    x = rmsnorm(h1, w[FFN_NORM], m.eps)
+    act = silu(x @ w[W_GATE].T) * (x @ w[W_UP].T)
+    h2 = h1 + act @ w[W_DOWN].T
+    return h2, k, v
+
+
+def lm_head(m: Model, h_last: np.ndarray) -> np.ndarray:
+    """Decode head: logits = RMSNorm(h^L; g_final) @ W_lm^T."""
+    return rmsnorm(h_last, m.w(FINAL_NORM), m.eps) @ m.w(LM_HEAD).T
+
+
+def prefill(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: Sequence[int],
+            want_logits: bool = True, start_layer: int = 0, start_hidden: Optional[np.ndarray] = None,
+            end_layer: Optional[int] = None):
+    """Teacher-forced causal forward over packed sequences (Section 4, Eq. (1)).
+
+    tokens int [N] packed back to back, lengths [B].  Returns (hidden {layer: [N, d]}, logits [N, V] or
+    None).  Layers are walked outermost so that only one layer's weights are alive at a time; each
+    sequence is processed on its own (sequences never interact).
+
+    `start_layer`/`start_hidden`/`end_layer` give the segment-local form of Section 5.6: begin from
+    recorded states entering block start_layer+1 instead of from the embedding, stop after block
+    end_layer.
+    """
+    tokens = np.asarray(tokens)
+    n = int(np.sum(lengths))
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    end_layer = m.L if end_layer is None else end_layer
+    if start_hidden is None:
+        emb = m.w(EMBED)
+        h = emb[tokens[:n]]
+        del emb
+    else:
+        h = np.array(start_hidden, dtype=np.float64)
+    hidden: Dict[int, np.ndarray] = {}
+    for l in range(start_layer, end_layer):
+        w = _layer_weights(m, l)
+        nxt = np.empty_like(h)
+        for b in range(len(lengths)):
+            lo, hi = int(cu[b]), int(cu[b + 1])
+            if hi == lo:
+                continue
+            pos = np.arange(hi - lo)
+            nxt[lo:hi], _, _ = _block(m, w, h[lo:hi], pos, None, None)
+        h = nxt
+        if (l + 1) in commit_layers:
+            hidden[l + 1] = h.copy()
+    logits = lm_head(m, h) if (want_logits and end_layer == m.L) else None
+    return hidden, logits
+
+
+def decode(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: Sequence[int],
+           want_logits: bool = True):
+    """Token-by-token generation-order forward with a KV cache (Section 5.5 recurrence).
+
+    Teacher-forced on `tokens`.  Every step processes ONE position of one sequence against the keys and
+    values cached from its earlier positions.  All layer weights are held (small models only).
+    Returns the same structure as `prefill`.
+    """
+    tokens = np.asarray(tokens)
+    n = int(np.sum(lengths))
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    emb = m.w(EMBED)
+    ws = [_layer_weights(m, l) for l in range(m.L)]
+    hidden = {l: np.empty((n, m.d), dtype=np.float64) for l in commit_layers}
+    last = np.empty((n, m.d), dtype=np.float64)
+    for b in range(len(lengths)):
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        kc: List[Optional[np.ndarray]] = [None] * m.L
+        vc: List[Optional[np.ndarray]] = [None] * m.L
+        for t in range(hi - lo):
+            h = emb[tokens[lo + t]][None, :]
+            pos = np.array([t])
+            for l in range(m.L):
+                h, kc[l], vc[l] = _block(m, ws[l], h, pos, kc[l], vc[l])
+                if (l + 1) in hidden:
+                    hidden[l + 1][lo + t] = h[0]
+            last[lo + t] = h[0]
+    logits = lm_head(m, last) if want_logits else None
+    return hidden, logits
+
+
+# ------------------------------------------------------------------------------------------------
+# comparison (Section 5.7)
+# ------------------------------------------------------------------------------------------------
+
+def compare_hidden(h_hat: np.ndarray, h_star: np.ndarray, tol_rel_l2: float, tol_max_abs: float):
+    """Per-token statistics of Delta = h_hat - h_star and the per-token pass bit.
+
+    h_hat [N, d] is the verifier's recomputation, h_star [N, d] the committed state (any stored dtype).
+    Returns dict of float64 [N] arrays: rel_l2 = ||Delta||_2 / max(||h_hat||_2, 1e-30),
+    max_abs = max|Delta|, mean_abs = mean|Delta| (the paper's example phi), mean_signed = mean Delta;
+    and ok [N] bool = (rel_l2 <= tol_rel_l2) and (max_abs <= tol_max_abs).
+
+    The denominator is the verifier's own state, which the committing party cannot scale.
+    A NaN anywhere in a row makes both comparisons false, so the position is rejected.
+    """
+    a = upcast(h_hat)
+    b = upcast(h_star)
+    with np.errstate(invalid="ignore", over="ignore"):
+        delta = a - b
+        e2 = np.sum(delta * delta, axis=-1)
+        n2 = np.sum(a * a, axis=-1)
+        rel = np.sqrt(e2) / np.maximum(np.sqrt(n2), TINY)
+        mx = np.max(np.abs(delta), axis=-1)
+        nanrow = np.isnan(delta).any(axis=-1)
+        mx = np.where(nanrow, np.nan, mx)
+        mean_abs = np.mean(np.abs(delta), axis=-1)
+        mean_signed = np.mean(delta, axis=-1)
+        ok = (rel <= tol_rel_l2) & (mx <= tol_max_abs)
+    return {"rel_l2": rel, "max_abs": mx, "mean_abs": mean_abs, "mean_signed": mean_signed, "ok": ok}
+
+
+def token_check(logits: np.ndarray, committed_argmax: np.ndarray, margin: float):
+    """TokenMatch with a margin: position passes iff max_v z[v] - z[a*] <= margin.
+
+    margin = 0 is the paper's exact match (the committed token must attain the maximum).
+    committed_argmax[n] = -1 skips position n (passes).  Out-of-range ids fail.
+    Returns (argmax [N] with lowest-index tie-break, gap [N] float64, ok [N] bool).
+    """
+    z = np.asarray(logits, dtype=np.float64)
+    n, v = z.shape
+    a = argmax_lowest(z)
+    top = z[np.arange(n), a]
+    cam = np.asarray(committed_argmax, dtype=np.int64)
+    valid = (cam >= 0) & (cam < v)
+    zc = z[np.arange(n), np.where(valid, cam, 0)]
+    gap = np.where(valid, top - zc, np.inf)
+    with np.errstate(invalid="ignore"):
+        ok = gap <= margin
+    skip = cam == -1
+    gap = np.where(skip, 0.0, gap)
+    ok = np.where(skip, True, ok)
+    return a, gap, ok
+
+
+def flags(hidden_ok: Sequence[np.ndarray], token_ok: Optional[np.ndarray]) -> np.ndarray:
+    """flag[n] = 1 (accept) iff every committed layer passes at n and the token check passes at n."""
+    f = np.ones_like(np.asarray(hidden_ok[0]), dtype=bool) if len(hidden_ok) else np.ones_like(token_ok, dtype=bool)
+    for ok in hidden_ok:
+        f &= np.asarray(ok, dtype=bool)
+    if token_ok is not None:
+        f &= np.asarray(token_ok, dtype=bool)
+    return f.astype(np.uint8)
+
+
+def summary(stats: Sequence[dict], token_ok: Optional[np.ndarray], flag: np.ndarray) -> dict:
+    """Batch-level numbers: reject counts, worst errors, and T_v = mean over tokens (and committed layers)
+    of the per-token mean absolute error (phi = MAE, Psi = mean in Section 5.7)."""
+    n = len(flag)
+    hid_ok = np.ones(n, dtype=bool)
+    for s in stats:
+        hid_ok &= s["ok"]
+    out = {
+        "n_tokens": n,
+        "n_rejected": int(n - int(np.sum(flag))),
+        "n_hidden_reject": int(np.sum(~hid_ok)),
+        "n_token_reject": int(np.sum(~np.asarray(token_ok, dtype=bool))) if token_ok is not None else 0,
+        "max_rel_l2": float(np.nanmax([np.nanmax(s["rel_l2"]) for s in stats])) if stats and n else 0.0,
+        "max_abs": float(np.nanmax([np.nanmax(s["max_abs"]) for s in stats])) if stats and n else 0.0,
+        "mean_mae": float(np.mean([np.mean(s["mean_abs"]) for s in stats])) if stats and n else 0.0,
+    }
+    return out
+
+
+def verify(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: Sequence[int],
+           committed_hidden: np.ndarray, committed_argmax: Optional[np.ndarray],
+           tol_rel_l2: float, tol_max_abs: float, tol_logit_margin: float):
+    """The whole hot path: prefill, compare at every committed layer, token check, flags, summary.
+
+    committed_hidden [C, N, d] in stored dtype.  Returns dict with hidden, logits, stats (list over C),
+    argmax, gap, token_ok, flags, summary.
+    """
+    hidden, logits = prefill(m, tokens, lengths, commit_layers, want_logits=committed_argmax is not None)
+    stats = [compare_hidden(hidden[l], committed_hidden[c], tol_rel_l2, tol_max_abs)
+             for c, l in enumerate(commit_layers)]
+    if committed_argmax is not None:
+        a, gap, tok_ok = token_check(logits, committed_argmax, tol_logit_margin)
+    else:
+        a, gap, tok_ok = None, None, None
+    f = flags([s["ok"] for s in stats], tok_ok)
+    return {"hidden": hidden, "logits": logits, "stats": stats, "argmax": a, "gap": gap, "token_ok": tok_ok,
+            "flags": f, "summary": summary(stats, tok_ok, f)}
