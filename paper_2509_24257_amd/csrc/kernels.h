@@ -1,0 +1,79 @@
+// Host-side launchers of the gfx950 kernels.  Every pointer is a device pointer unless it says otherwise;
+// every launcher enqueues on `s` and returns without synchronising.  Shapes are validated by the caller
+// (engine.hip) before any launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/verillm.h"
+
+namespace vl {
+
+// ---- elementwise / row kernels (kernels_rows.hip) ------------------------------------------------
+// resid[n,:] = E[id, :] with id = tok[row_tok ? row_tok[n] : n].  An id outside [0,vocab) reads row 0 instead and
+// clears valid[dst ? dst[n] : n] (valid may be NULL); activations therefore stay finite whatever the ids are.
+void launch_embed(const void* E, int dtype, const int32_t* tok, const int32_t* row_tok, float* resid,
+                  uint8_t* valid, const int32_t* dst, int64_t rows, int d, int vocab, hipStream_t s);
+// out[n,:] = x[n,:] * rsqrt(mean(x[n,:]^2) + eps) * gain, written in `dtype`.
+void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int64_t rows, int d, float eps,
+                    hipStream_t s);
+// Rotate query and key heads of qkv [rows][(hq+2hkv)*hd] in place using the cos/sin table
+// cs[pos][hd/2] (float2 = cos, sin).
+void launch_rope(void* qkv, int dtype, const int32_t* pos, const float2* cs, int64_t rows, int hq, int hkv,
+                 int hd, hipStream_t s);
+// vt[g][c][ vt_col[n] ] = V head g, channel c of token n (bf16); ldv = row pitch of vt in elements.
+void launch_transpose_v(const void* qkv, void* vt, const int32_t* vt_col, int64_t rows, int hq, int hkv, int hd,
+                        int64_t ldv, hipStream_t s);
+// Copy K and V heads of qkv rows into the KV cache: cache row index = cache_row[n]; each cache row holds
+// hkv*hd elements.
+void launch_kv_store(const void* qkv, int dtype, void* kcache, void* vcache, const int32_t* cache_row,
+                     int64_t rows, int hq, int hkv, int hd, hipStream_t s);
+// out[(dst ? dst[n] : n), :] = resid[n, :] converted to `dtype`.
+void launch_store_hidden(const float* resid, void* out, int dtype, const int32_t* dst, int64_t rows, int d,
+                         hipStream_t s);
+void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, int64_t rows, hipStream_t s);
+void launch_fill_u8(uint8_t* p, uint8_t v, int64_t n, hipStream_t s);
+
+// ---- simple tiled GEMM on the vector ALUs (kernels_gemm_simple.hip) ------------------------------
+enum EpiKind { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_ADD_RESID = 2, EPI_SWIGLU = 3 };
+// C[M,N] = A[M,K] * W[N,K]^T, fp32 accumulate.  A and W are `dtype`.
+//   EPI_STORE     : out [M][N] in dtype
+//   EPI_STORE_F32 : out [M][N] float
+//   EPI_ADD_RESID : out [M][N] float, out += C
+//   EPI_SWIGLU    : W rows interleave gate/up in blocks of `ib` rows (ib gate rows, ib up rows, ...);
+//                   out [M][N/2] in dtype = silu(gate) * up
+void launch_gemm_simple(const void* A, const void* W, int dtype, int M, int N, int K, int epi, void* out, int ib,
+                        hipStream_t s);
+
+// ---- bf16 matrix-core GEMM (kernels_gemm_mfma.hip) -----------------------------------------------
+// Same contract as launch_gemm_simple with dtype = bf16; K % 64 == 0; EPI_SWIGLU interleaves in blocks of 32
+// rows and needs N % 64 == 0.
+void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s);
+
+// ---- attention ------------------------------------------------------------------------------------
+// One wave per (query row, query head), online softmax over keys 0..npos[row].
+//   q    : [rows][q_stride] elements, head j at offset j*hd
+//   k, v : key/value t of row r, kv head g at  base[(kv_row0[r] + t) * kv_stride + g*hd]
+void launch_attn_rowwise(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
+                         const int32_t* kv_row0, const int32_t* npos, void* out, int dtype, int64_t rows, int hq,
+                         int hkv, int hd, hipStream_t s);
+// Causal GQA flash attention on the matrix cores over packed sequences.
+//   qkv bf16 [N][(hq+2hkv)*hd], vt bf16 [hkv][hd][ldv] (values transposed, column = vt column of the token),
+//   tiles: host-built work list (see engine), out bf16 [N][hq*hd].
+struct AttnTile { int32_t q_row0, q_rows, kv_row0, kv_len, vt_col0, pos0; };  // one 128-query tile of a sequence:
+//   q_row0  packed row of its first query, q_rows valid queries (<= 128), pos0 position of the first query,
+//   kv_row0 packed row of the sequence's first token, kv_len = pos0 + q_rows keys are visible to the tile,
+//   vt_col0 column of the sequence's first token in vt (a multiple of 8)
+void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
+                      void* out, int hq, int hkv, int hd, hipStream_t s);
+
+// ---- compare / argmax / flags (kernels_compare.hip) ------------------------------------------------
+void launch_compare(const float* h_hat, const void* committed, int hidden_dtype, int64_t rows, int d, float tol_rel,
+                    float tol_abs, vl_tok_stats* stats, uint8_t* ok_and, uint8_t* ok_set, hipStream_t s);
+void launch_argmax(const float* logits, int64_t rows, int vocab, const int32_t* committed, float margin,
+                   int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s);
+struct DevSummary { unsigned long long n_rejected, n_hidden_reject, n_token_reject; float max_rel, max_abs, mean_mae; };
+void launch_finalize(const uint8_t* hid_ok, const uint8_t* tok_ok, const vl_tok_stats* stats, int C, int64_t rows,
+                     uint8_t* flags, DevSummary* out, hipStream_t s);
+
+}  // namespace vl

@@ -1,0 +1,209 @@
+// The comparison stage (Section 5.7 "Comparison and On-Chain Commitment"): elementwise discrepancy
+// Delta = S_hat - S between the recomputed and the committed hidden states, reduced per token to
+// rel-L2 / max-abs / mean-abs / mean-signed and thresholded; the TokenMatch check on the logits; the final
+// per-position flags and the batch summary.  All three kernels are pure HBM streaming: one wave owns one
+// row (compare) or one workgroup owns one row (argmax), every load is a contiguous 16 bytes per lane, and all
+// reductions are butterfly shuffles in a fixed order, so results are bit-identical from run to run.
+#include "common.h"
+#include "kernels.h"
+
+namespace vl {
+
+// ---------------------------------------------------------------- compare: one wave per token row
+template <typename TC> struct Load8;
+template <> struct Load8<bf16> {
+    static __device__ __forceinline__ void load(const bf16* p, float (&v)[8]) {
+        const bf16x8 t = *(const bf16x8*)p;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (float)t[i];
+    }
+};
+template <> struct Load8<float> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+        const float4 a = ((const float4*)p)[0], b = ((const float4*)p)[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+};
+
+template <typename TC>
+__global__ __launch_bounds__(256) void compare_kernel(const float* __restrict__ h_hat, const TC* __restrict__ h_star,
+                                                      int64_t rows, int d, float tol_rel, float tol_abs,
+                                                      vl_tok_stats* __restrict__ stats, uint8_t* __restrict__ ok_and,
+                                                      uint8_t* __restrict__ ok_set) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;                      // whole wave leaves together; no barrier below
+    const float* a = h_hat + row * (int64_t)d;
+    const TC* b = h_star + row * (int64_t)d;
+    float e2 = 0.f, n2 = 0.f, e1 = 0.f, es = 0.f, emax = 0.f;
+    const int chunks = d >> 3;
+#pragma unroll 4
+    for (int c = lane; c < chunks; c += WAVE) {
+        float x[8], y[8];
+        Load8<float>::load(a + 8 * c, x);
+        Load8<TC>::load(b + 8 * c, y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float dl = x[i] - y[i];
+            e2 = fmaf(dl, dl, e2);
+            n2 = fmaf(x[i], x[i], n2);
+            e1 += fabsf(dl);
+            es += dl;
+            emax = fmaxf(emax, fabsf(dl));        // fmaxf drops NaN; a NaN row is recovered from e2 below
+        }
+    }
+    e2 = wave_sum(e2);
+    n2 = wave_sum(n2);
+    e1 = wave_sum(e1);
+    es = wave_sum(es);
+    emax = wave_max(emax);
+    if (lane == 0) {
+        const float rel = sqrtf(e2) / fmaxf(sqrtf(n2), 1e-30f);
+        if (e2 != e2) emax = e2;                  // NaN anywhere in the row -> max_abs is NaN
+        const float inv_d = 1.0f / (float)d;
+        vl_tok_stats st;
+        st.rel_l2 = rel;
+        st.max_abs = emax;
+        st.mean_abs = e1 * inv_d;
+        st.mean_signed = es * inv_d;
+        if (stats) stats[row] = st;
+        const uint8_t ok = (rel <= tol_rel) && (emax <= tol_abs);   // NaN compares false -> reject
+        if (ok_and) ok_and[row] = ok_and[row] & ok;
+        if (ok_set) ok_set[row] = ok;
+    }
+}
+
+void launch_compare(const float* h_hat, const void* committed, int hidden_dtype, int64_t rows, int d, float tol_rel,
+                    float tol_abs, vl_tok_stats* stats, uint8_t* ok_and, uint8_t* ok_set, hipStream_t s) {
+    if (rows <= 0) return;
+    dim3 grid((unsigned)((rows + 3) / 4));
+    if (hidden_dtype == VL_BF16)
+        compare_kernel<bf16><<<grid, 256, 0, s>>>(h_hat, (const bf16*)committed, rows, d, tol_rel, tol_abs, stats, ok_and,
+                                                  ok_set);
+    else
+        compare_kernel<float><<<grid, 256, 0, s>>>(h_hat, (const float*)committed, rows, d, tol_rel, tol_abs, stats,
+                                                   ok_and, ok_set);
+}
+
+// ---------------------------------------------------------------- argmax + TokenMatch: one workgroup per row
+__device__ __forceinline__ void take_better(float& bv, int& bi, float v, int i) {
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int vocab,
+                                                     const int32_t* __restrict__ committed, float margin,
+                                                     int32_t* __restrict__ out_argmax, float* __restrict__ out_gap,
+                                                     uint8_t* __restrict__ out_ok) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    const int64_t row = blockIdx.x;
+    const float* z = logits + row * (int64_t)vocab;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    if ((vocab & 3) == 0) {
+        const float4* z4 = (const float4*)z;
+        const int n4 = vocab >> 2;
+#pragma unroll 4
+        for (int i = threadIdx.x; i < n4; i += 256) {
+            const float4 t = z4[i];
+            // ascending index within the lane, strict '>' keeps the lowest index among equals
+            if (t.x > bv) { bv = t.x; bi = 4 * i; }
+            if (t.y > bv) { bv = t.y; bi = 4 * i + 1; }
+            if (t.z > bv) { bv = t.z; bi = 4 * i + 2; }
+            if (t.w > bv) { bv = t.w; bi = 4 * i + 3; }
+        }
+    } else {
+        for (int i = threadIdx.x; i < vocab; i += 256) {
+            const float t = z[i];
+            if (t > bv) { bv = t; bi = i; }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, WAVE);
+        const int oi = __shfl_xor(bi, o, WAVE);
+        take_better(bv, bi, ov, oi);
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) take_better(bv, bi, sv[w], si[w]);
+        if (bi == 0x7fffffff) bi = 0;                          // every logit NaN
+        float gap = 0.f;
+        uint8_t ok = 1;
+        if (committed) {
+            const int c = committed[row];
+            if (c == -1) { gap = 0.f; ok = 1; }
+            else if (c < 0 || c >= vocab) { gap = INFINITY; ok = 0; }
+            else { gap = bv - z[c]; ok = (gap <= margin); }     // NaN compares false -> reject
+        }
+        if (out_argmax) out_argmax[row] = bi;
+        if (out_gap) out_gap[row] = gap;
+        if (out_ok) out_ok[row] = ok;
+    }
+}
+
+void launch_argmax(const float* logits, int64_t rows, int vocab, const int32_t* committed, float margin,
+                   int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s) {
+    if (rows <= 0) return;
+    argmax_kernel<<<dim3((unsigned)rows), 256, 0, s>>>(logits, vocab, committed, margin, out_argmax, out_gap, out_ok);
+}
+
+// ---------------------------------------------------------------- flags + summary: one workgroup, fixed order
+__global__ __launch_bounds__(1024) void finalize_kernel(const uint8_t* __restrict__ hid_ok, const uint8_t* __restrict__ tok_ok,
+                                                        const vl_tok_stats* __restrict__ stats, int C, int64_t rows,
+                                                        uint8_t* __restrict__ flags, DevSummary* __restrict__ out) {
+    __shared__ unsigned long long s_rej[16], s_hid[16], s_tok[16];
+    __shared__ float s_mr[16], s_ma[16];
+    __shared__ double s_sum[16];
+    unsigned long long rej = 0, hid = 0, tok = 0;
+    for (int64_t n = threadIdx.x; n < rows; n += 1024) {
+        const uint8_t h = hid_ok[n], t = tok_ok[n];
+        const uint8_t f = h & t;
+        flags[n] = f;
+        rej += (f == 0);
+        hid += (h == 0);
+        tok += (t == 0);
+    }
+    float mr = 0.f, ma = 0.f;
+    double sum = 0.0;
+    const int64_t total = rows * (int64_t)C;
+    for (int64_t i = threadIdx.x; i < total; i += 1024) {
+        const vl_tok_stats st = stats[i];
+        mr = fmaxf(mr, st.rel_l2);               // fmaxf ignores NaN, like a nan-max
+        ma = fmaxf(ma, st.max_abs);
+        sum += (double)st.mean_abs;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        rej += __shfl_xor(rej, o, WAVE);
+        hid += __shfl_xor(hid, o, WAVE);
+        tok += __shfl_xor(tok, o, WAVE);
+        mr = fmaxf(mr, __shfl_xor(mr, o, WAVE));
+        ma = fmaxf(ma, __shfl_xor(ma, o, WAVE));
+        sum += __shfl_xor(sum, o, WAVE);
+    }
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_rej[w] = rej; s_hid[w] = hid; s_tok[w] = tok; s_mr[w] = mr; s_ma[w] = ma; s_sum[w] = sum; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < 16; ++i) {
+            rej += s_rej[i]; hid += s_hid[i]; tok += s_tok[i];
+            mr = fmaxf(mr, s_mr[i]); ma = fmaxf(ma, s_ma[i]); sum += s_sum[i];
+        }
+        out->n_rejected = rej;
+        out->n_hidden_reject = hid;
+        out->n_token_reject = tok;
+        out->max_rel = mr;
+        out->max_abs = ma;
+        out->mean_mae = (float)(total > 0 ? sum / (double)total : 0.0);
+    }
+}
+
+void launch_finalize(const uint8_t* hid_ok, const uint8_t* tok_ok, const vl_tok_stats* stats, int C, int64_t rows,
+                     uint8_t* flags, DevSummary* out, hipStream_t s) {
+    finalize_kernel<<<1, 1024, 0, s>>>(hid_ok, tok_ok, stats, C, rows, flags, out);
+}
+
+}  // namespace vl

@@ -1,0 +1,216 @@
+// Row-wise HBM-bound kernels of the decoder block: embedding gather, RMSNorm, rotary embedding, value
+// transpose, KV-cache store, hidden-state store.  One workgroup (256 lanes = 4 waves) per token row unless
+// noted; loads and stores are contiguous along the row so each wave touches whole cache lines.
+#include "common.h"
+#include "kernels.h"
+
+namespace vl {
+
+constexpr int ROW_THREADS = 256;
+
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < ROW_THREADS / WAVE; ++i) t += red[i];
+    __syncthreads();
+    return t;
+}
+
+// ---------------------------------------------------------------- embedding (S_1 = Embed(x), Section 5.5)
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok,
+                                                             const int32_t* __restrict__ row_tok,
+                                                             float* __restrict__ resid, uint8_t* __restrict__ valid,
+                                                             const int32_t* __restrict__ dst, int d, int vocab) {
+    const int64_t n = blockIdx.x;
+    int id = tok[row_tok ? row_tok[n] : n];
+    if (id < 0 || id >= vocab) {
+        id = 0;
+        if (valid && threadIdx.x == 0) valid[dst ? dst[n] : n] = 0;
+    }
+    float* out = resid + n * (int64_t)d;
+    const T* src = E + (int64_t)id * d;
+    for (int i = threadIdx.x; i < d; i += ROW_THREADS) out[i] = to_f32(src[i]);
+}
+
+void launch_embed(const void* E, int dtype, const int32_t* tok, const int32_t* row_tok, float* resid, uint8_t* valid,
+                  const int32_t* dst, int64_t rows, int d, int vocab, hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == VL_BF16)
+        embed_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const bf16*)E, tok, row_tok, resid, valid, dst, d,
+                                                                       vocab);
+    else
+        embed_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const float*)E, tok, row_tok, resid, valid, dst,
+                                                                        d, vocab);
+}
+
+// ---------------------------------------------------------------- RMSNorm
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                               T* __restrict__ out, int d, float eps) {
+    __shared__ float red[ROW_THREADS / WAVE];
+    const int64_t n = blockIdx.x;
+    const float4* xr = (const float4*)(x + n * (int64_t)d);
+    const float4* g4 = (const float4*)gain;
+    const int d4 = d >> 2;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d4; i += ROW_THREADS) {
+        const float4 v = xr[i];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    ss = block_sum(ss, red);
+    const float r = 1.0f / sqrtf(ss / (float)d + eps);
+    T* o = out + n * (int64_t)d;
+    for (int i = threadIdx.x; i < d4; i += ROW_THREADS) {
+        const float4 v = xr[i];
+        const float4 g = g4[i];
+        o[4 * i + 0] = from_f32<T>(v.x * r * g.x);
+        o[4 * i + 1] = from_f32<T>(v.y * r * g.y);
+        o[4 * i + 2] = from_f32<T>(v.z * r * g.z);
+        o[4 * i + 3] = from_f32<T>(v.w * r * g.w);
+    }
+}
+
+void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int64_t rows, int d, float eps,
+                    hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == VL_BF16)
+        rmsnorm_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (bf16*)out, d, eps);
+    else
+        rmsnorm_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (float*)out, d, eps);
+}
+
+// ---------------------------------------------------------------- rotary embedding, in place on Q and K
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void rope_kernel(T* __restrict__ qkv, const int32_t* __restrict__ pos,
+                                                            const float2* __restrict__ cs, int hq, int hkv, int hd) {
+    const int64_t n = blockIdx.x;
+    const int half = hd >> 1;
+    const int p = pos[n];
+    T* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd;
+    const float2* tab = cs + (int64_t)p * half;
+    const int pairs = (hq + hkv) * half;           // query heads then key heads are contiguous in the row
+    for (int i = threadIdx.x; i < pairs; i += ROW_THREADS) {
+        const int h = i / half, c = i - h * half;
+        const float2 t = tab[c];
+        T* a = row + h * hd + c;
+        const float x1 = to_f32(a[0]), x2 = to_f32(a[half]);
+        a[0] = from_f32<T>(x1 * t.x - x2 * t.y);
+        a[half] = from_f32<T>(x2 * t.x + x1 * t.y);
+    }
+}
+
+void launch_rope(void* qkv, int dtype, const int32_t* pos, const float2* cs, int64_t rows, int hq, int hkv, int hd,
+                 hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == VL_BF16)
+        rope_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((bf16*)qkv, pos, cs, hq, hkv, hd);
+    else
+        rope_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((float*)qkv, pos, cs, hq, hkv, hd);
+}
+
+// ---------------------------------------------------------------- V transpose for the matrix-core attention
+// Tile of 64 tokens x 64 channels through LDS so that both the read (along channels) and the write
+// (along tokens) are contiguous.  grid = (ceil(rows/64), hkv*hd/64).
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ vt,
+                                                           const int32_t* __restrict__ vt_col, int64_t rows, int hq,
+                                                           int hkv, int hd, int64_t ldv) {
+    __shared__ bf16 tile[64][66];
+    __shared__ int32_t cols[64];
+    const int64_t n0 = (int64_t)blockIdx.x * 64;
+    const int c0 = blockIdx.y * 64;                      // channel offset within the hkv*hd value block
+    const int64_t pitch = (int64_t)(hq + 2 * hkv) * hd;
+    const bf16* vbase = qkv + (int64_t)(hq + hkv) * hd + c0;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    if (threadIdx.x < 64) cols[threadIdx.x] = (n0 + threadIdx.x < rows) ? vt_col[n0 + threadIdx.x] : -1;
+    for (int r = ty; r < 64; r += 4) {
+        const int64_t n = n0 + r;
+        tile[r][tx] = (n < rows) ? vbase[n * pitch + tx] : (bf16)0.f;
+    }
+    __syncthreads();
+    // consecutive tokens of one sequence have consecutive vt columns, so lanes write contiguous runs
+    for (int c = ty; c < 64; c += 4) {
+        const int col = cols[tx];
+        if (col >= 0) vt[(int64_t)(c0 + c) * ldv + col] = tile[tx][c];
+    }
+}
+
+void launch_transpose_v(const void* qkv, void* vt, const int32_t* vt_col, int64_t rows, int hq, int hkv, int hd,
+                        int64_t ldv, hipStream_t s) {
+    if (rows <= 0) return;
+    dim3 grid((unsigned)((rows + 63) / 64), (unsigned)(hkv * hd / 64));
+    transpose_v_kernel<<<grid, 256, 0, s>>>((const bf16*)qkv, (bf16*)vt, vt_col, rows, hq, hkv, hd, ldv);
+}
+
+// ---------------------------------------------------------------- KV-cache store
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void kv_store_kernel(const T* __restrict__ qkv, T* __restrict__ kc,
+                                                                T* __restrict__ vc, const int32_t* __restrict__ cache_row,
+                                                                int hq, int hkv, int hd) {
+    const int64_t n = blockIdx.x;
+    const int w = hkv * hd;
+    const T* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd + (int64_t)hq * hd;
+    const int64_t dst = (int64_t)cache_row[n] * w;
+    for (int i = threadIdx.x; i < w; i += ROW_THREADS) {
+        kc[dst + i] = row[i];
+        vc[dst + i] = row[w + i];
+    }
+}
+
+void launch_kv_store(const void* qkv, int dtype, void* kcache, void* vcache, const int32_t* cache_row, int64_t rows,
+                     int hq, int hkv, int hd, hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == VL_BF16)
+        kv_store_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const bf16*)qkv, (bf16*)kcache, (bf16*)vcache,
+                                                                          cache_row, hq, hkv, hd);
+    else
+        kv_store_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const float*)qkv, (float*)kcache,
+                                                                           (float*)vcache, cache_row, hq, hkv, hd);
+}
+
+// ---------------------------------------------------------------- hidden-state store (commitments out)
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void store_hidden_kernel(const float* __restrict__ resid, T* __restrict__ out,
+                                                                    const int32_t* __restrict__ dst, int d) {
+    const int64_t n = blockIdx.x;
+    const int64_t o = dst ? (int64_t)dst[n] : n;
+    const float* src = resid + n * (int64_t)d;
+    T* dp = out + o * (int64_t)d;
+    for (int i = threadIdx.x; i < d; i += ROW_THREADS) dp[i] = from_f32<T>(src[i]);
+}
+
+void launch_store_hidden(const float* resid, void* out, int dtype, const int32_t* dst, int64_t rows, int d,
+                         hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == VL_BF16)
+        store_hidden_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(resid, (bf16*)out, dst, d);
+    else
+        store_hidden_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(resid, (float*)out, dst, d);
+}
+
+__global__ void scatter_i32_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ out,
+                                   const int32_t* __restrict__ dst, int64_t rows) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < rows) out[dst ? dst[i] : i] = src[i];
+}
+
+void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, int64_t rows, hipStream_t s) {
+    if (rows <= 0) return;
+    scatter_i32_kernel<<<dim3((unsigned)((rows + 255) / 256)), 256, 0, s>>>(src, out, dst, rows);
+}
+
+__global__ void fill_u8_kernel(uint8_t* p, uint8_t v, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+void launch_fill_u8(uint8_t* p, uint8_t v, int64_t n, hipStream_t s) {
+    if (n <= 0) return;
+    fill_u8_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, s>>>(p, v, n);
+}
+
+}  // namespace vl

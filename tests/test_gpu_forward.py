@@ -1,0 +1,290 @@
+"""End-to-end GPU parity of the verification hot path against the CPU oracle, through the C ABI.
+
+Small shapes that still span several GEMM / attention tiles and ragged tails.  Tolerances:
+  fp32 model : fp32 accumulation over K <= 688 terms, 2 layers -> hidden rel-L2 <= 1e-5, logits <= 1e-4 abs
+  bf16 model : every GEMM operand is rounded to bf16 (2^-9 relative) -> hidden rel-L2 <= 2e-2 per committed
+               layer, logits max-abs <= 5e-2, argmax equal wherever the oracle's top-2 gap is >= 0.1
+Flags must be bit-exact: honest noise is far below the acceptance tolerance, tampering far above it.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_24257_amd as P
+import synth
+from oracle import verillm_oracle as O
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_commitments(om, wl, x, mode="prefill"):
+    hid, z = (O.decode if mode == "decode" else O.prefill)(om, x, wl.lengths, wl.commit_layers)
+    committed = np.stack([hid[l] for l in wl.commit_layers]).astype(np.float32) if wl.commit_layers else \
+        np.zeros((0, wl.n_tokens, wl.model.d_model), np.float32)
+    return hid, z, committed
+
+
+def check_verify_against_oracle(ctx, om, wl, x, committed_f32, z, tol_hidden, tol_logit, tie_gap):
+    """Tamper, run GPU verify and oracle verify on identical inputs, compare everything."""
+    n = wl.n_tokens
+    pos = synth.tamper_positions(wl)
+    com_t = synth.tamper_hidden(wl, committed_f32, pos) if len(wl.commit_layers) else committed_f32
+    com_st = H.stored(com_t, wl.hidden_dtype)
+    if wl.check_argmax:
+        cam = O.argmax_lowest(z).astype(np.int32)
+        cam_t, changed = synth.tamper_argmax(wl, cam, pos, wrong_tokens=np.argmin(z, axis=1))
+    else:
+        cam_t, changed = None, []
+    flags, stats, sm = H.run_verify(ctx, wl, x, com_st, cam_t)
+    ref = O.verify(om, x, wl.lengths, wl.commit_layers, com_st, cam_t, wl.tol_rel_l2, wl.tol_max_abs, wl.tol_logit_margin)
+    expect = np.ones(n, np.uint8)
+    if len(wl.commit_layers):
+        expect[pos] = 0
+    else:
+        expect[np.asarray(changed, dtype=np.int64)] = 0
+    np.testing.assert_array_equal(ref["flags"], expect)                  # the oracle sees the planted mask
+    np.testing.assert_array_equal(flags, ref["flags"])                   # and the GPU agrees bit for bit
+    for c in range(len(wl.commit_layers)):
+        assert np.abs(stats[c]["rel_l2"] - ref["stats"][c]["rel_l2"]).max() <= tol_hidden * 1.5
+        scale = np.abs(com_t[c]).max()
+        assert np.abs(stats[c]["max_abs"] - ref["stats"][c]["max_abs"]).max() <= tol_hidden * scale * 4
+        assert np.abs(stats[c]["mean_abs"] - ref["stats"][c]["mean_abs"]).max() <= tol_hidden * scale
+    assert sm["n_tokens"] == n and sm["n_rejected"] == ref["summary"]["n_rejected"]
+    assert sm["n_hidden_reject"] == ref["summary"]["n_hidden_reject"]
+    assert sm["n_token_reject"] == ref["summary"]["n_token_reject"]
+    if len(wl.commit_layers):
+        assert sm["max_rel_l2"] == pytest.approx(ref["summary"]["max_rel_l2"], abs=tol_hidden * 1.5, rel=0.05)
+        # mean|Delta| moves by at most the GPU-vs-oracle noise, itself <= tol_hidden relative to the state's size
+        assert sm["mean_mae"] == pytest.approx(ref["summary"]["mean_mae"], abs=tol_hidden * float(np.abs(com_t).mean()) + 1e-7)
+        assert sm["mean_mae"] == pytest.approx(float(np.mean([s["mean_abs"].mean() for s in stats])), rel=1e-4)
+    if wl.check_argmax:
+        zg = H.get_logits(ctx, 0, n, wl.model.vocab)
+        assert np.abs(zg - z).max() <= tol_logit
+        a_gpu, gap_gpu = H.get_argmax(ctx, 0, n)
+        srt = np.sort(z, axis=1)
+        clear = (srt[:, -1] - srt[:, -2]) >= tie_gap
+        np.testing.assert_array_equal(a_gpu[clear], ref["argmax"][clear])
+        assert np.abs(gap_gpu - ref["gap"]).max() <= 2 * tol_logit
+    assert sm["ms_forward"] > 0 and 0 <= sm["ms_compare"] <= sm["ms_forward"]
+    return flags, stats, sm
+
+
+# ====================================================================================== tiny fp32 model
+@pytest.fixture(scope="module")
+def tiny():
+    wl = synth.workload(0)
+    ctx = H.make_ctx(wl.model, 256, 4, 256)
+    om = H.oracle_model(wl.model)
+    x = synth.tokens(wl)
+    yield ctx, om, wl, x
+    ctx.close()
+
+
+def test_tiny_f32_prefill_states_match_oracle(tiny):
+    ctx, om, wl, x = tiny
+    say("tiny f32 prefill_commit vs oracle prefill")
+    hid, z, _ = oracle_commitments(om, wl, x)
+    val, _, amax = H.run_commit(ctx, wl, x, "prefill")
+    for c, l in enumerate(wl.commit_layers):
+        assert H.rel_l2_rows(val[c], hid[l]).max() <= 1e-5
+    zg = H.get_logits(ctx, 0, wl.n_tokens, wl.model.vocab)
+    assert np.abs(zg - z).max() <= 1e-4
+    srt = np.sort(z, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) >= 2e-3
+    np.testing.assert_array_equal(amax[clear], O.argmax_lowest(z)[clear])
+
+
+def test_tiny_f32_decode_commit_matches_oracle_decode_and_gpu_prefill(tiny):
+    ctx, om, wl, x = tiny
+    say("tiny f32 decode_commit (token by token) vs oracle decode")
+    hid, z, _ = oracle_commitments(om, wl, x, "decode")
+    val_d, _, amax_d = H.run_commit(ctx, wl, x, "decode", prompt_lens=None)
+    for c, l in enumerate(wl.commit_layers):
+        assert H.rel_l2_rows(val_d[c], hid[l]).max() <= 1e-5
+    say("tiny f32 decode_commit with a prefilled prompt")
+    val_p, _, amax_p = H.run_commit(ctx, wl, x, "decode", prompt_lens=wl.prompt_lens)
+    val_f, _, amax_f = H.run_commit(ctx, wl, x, "prefill")
+    for c in range(len(wl.commit_layers)):
+        # honest decode-vs-prefill noise must sit far below the acceptance tolerance (calibration of tau)
+        assert H.rel_l2_rows(val_d[c], val_f[c]).max() <= wl.tol_rel_l2 / 2
+        assert H.rel_l2_rows(val_p[c], val_f[c]).max() <= wl.tol_rel_l2 / 2
+    srt = np.sort(z, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) >= 2e-3
+    np.testing.assert_array_equal(amax_d[clear], O.argmax_lowest(z)[clear])
+    np.testing.assert_array_equal(amax_p[clear], O.argmax_lowest(z)[clear])
+
+
+def test_tiny_f32_verify_flags_bit_exact_on_tampered_commitments(tiny):
+    ctx, om, wl, x = tiny
+    say("tiny f32 verify: oracle decode commitments, 4 tampered positions")
+    _, z, committed = oracle_commitments(om, wl, x, "decode")
+    check_verify_against_oracle(ctx, om, wl, x, committed, z, tol_hidden=1e-5, tol_logit=1e-4, tie_gap=2e-3)
+
+
+def test_tiny_f32_gpu_commitments_verify_clean_and_tamper_is_caught(tiny):
+    ctx, om, wl, x = tiny
+    say("tiny f32 verify on the library's own decode commitments")
+    val, st, amax = H.run_commit(ctx, wl, x, "decode", prompt_lens=wl.prompt_lens)
+    flags, stats, sm = H.run_verify(ctx, wl, x, st, amax)
+    assert flags.all() and sm["n_rejected"] == 0 and sm["max_rel_l2"] < wl.tol_rel_l2 / 2
+    pos = synth.tamper_positions(wl)
+    st_t = H.stored(synth.tamper_hidden(wl, val, pos), wl.hidden_dtype)
+    flags, _, sm = H.run_verify(ctx, wl, x, st_t, amax)
+    expect = np.ones(wl.n_tokens, np.uint8)
+    expect[pos] = 0
+    np.testing.assert_array_equal(flags, expect)
+    assert sm["n_rejected"] == len(pos)
+
+
+# ====================================================================================== small bf16 GQA model
+SMALL_LENGTHS = [37, 128, 1, 200, 64, 0, 259]
+
+
+@pytest.fixture(scope="module")
+def small_bf16():
+    m = synth.small_model("bf16", random_gains=True)
+    wl = synth.small_workload(m, SMALL_LENGTHS, [1, 3], tamper_count=9, seed=3)
+    ctx = H.make_ctx(m, 1024, 8, 512)
+    om = H.oracle_model(m)
+    x = synth.tokens(wl)
+    yield ctx, om, wl, x
+    ctx.close()
+
+
+def test_small_bf16_prefill_states_match_oracle(small_bf16):
+    ctx, om, wl, x = small_bf16
+    say("small bf16 prefill_commit vs oracle (varlen, GQA 4/2, hd 64)")
+    hid, z, _ = oracle_commitments(om, wl, x)
+    val, _, amax = H.run_commit(ctx, wl, x, "prefill")
+    for c, l in enumerate(wl.commit_layers):
+        r = H.rel_l2_rows(val[c], hid[l])
+        print("layer", l, "rel-L2 max", r.max(), "mean", r.mean(), flush=True)
+        assert r.max() <= 2e-2
+    zg = H.get_logits(ctx, 0, wl.n_tokens, wl.model.vocab)
+    print("logit max-abs err", np.abs(zg - z).max(), flush=True)
+    assert np.abs(zg - z).max() <= 5e-2
+    srt = np.sort(z, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) >= 0.1
+    np.testing.assert_array_equal(amax[clear], O.argmax_lowest(z)[clear])
+
+
+def test_small_bf16_verify_flags_bit_exact(small_bf16):
+    ctx, om, wl, x = small_bf16
+    say("small bf16 verify on oracle commitments with tampering")
+    _, z, committed = oracle_commitments(om, wl, x)
+    check_verify_against_oracle(ctx, om, wl, x, committed, z, tol_hidden=2e-2, tol_logit=5e-2, tie_gap=0.1)
+
+
+def test_small_bf16_decode_commit_both_forms(small_bf16):
+    ctx, om, wl, x = small_bf16
+    say("small bf16 decode_commit: all token-by-token")
+    hid, z, _ = oracle_commitments(om, wl, x)
+    val_d, st_d, amax_d = H.run_commit(ctx, wl, x, "decode", prompt_lens=None)
+    say("small bf16 decode_commit: prompt prefilled")
+    val_p, st_p, amax_p = H.run_commit(ctx, wl, x, "decode", prompt_lens=wl.prompt_lens)
+    val_f, _, _ = H.run_commit(ctx, wl, x, "prefill")
+    for c, l in enumerate(wl.commit_layers):
+        assert H.rel_l2_rows(val_d[c], hid[l]).max() <= 2e-2
+        assert H.rel_l2_rows(val_p[c], hid[l]).max() <= 2e-2
+        honest = max(H.rel_l2_rows(val_d[c], val_f[c]).max(), H.rel_l2_rows(val_p[c], val_f[c]).max())
+        print("honest decode-vs-prefill rel-L2", honest, flush=True)
+        assert honest <= wl.tol_rel_l2 / 2
+    srt = np.sort(z, axis=1)
+    clear = (srt[:, -1] - srt[:, -2]) >= 0.1
+    np.testing.assert_array_equal(amax_d[clear], O.argmax_lowest(z)[clear])
+    np.testing.assert_array_equal(amax_p[clear], O.argmax_lowest(z)[clear])
+    say("small bf16 verify of the decode commitments")
+    flags, _, sm = H.run_verify(ctx, wl, x, st_p, amax_p)
+    assert flags.all() and sm["n_rejected"] == 0
+
+
+def test_small_bf16_results_are_bit_reproducible_and_batch_independent(small_bf16):
+    ctx, om, wl, x = small_bf16
+    say("small bf16 determinism")
+    val1, st1, a1 = H.run_commit(ctx, wl, x, "prefill")
+    val2, st2, a2 = H.run_commit(ctx, wl, x, "prefill")
+    assert st1.tobytes() == st2.tobytes() and a1.tobytes() == a2.tobytes()
+    say("small bf16 one sequence alone vs inside the batch")
+    cu = synth.cu_seqlens(wl.lengths)
+    b = 3
+    lo, hi = int(cu[b]), int(cu[b + 1])
+    wl1 = synth.small_workload(wl.model, [wl.lengths[b]], wl.commit_layers)
+    v_alone, _, _ = H.run_commit(ctx, wl1, x[lo:hi], "prefill")
+    for c in range(len(wl.commit_layers)):
+        assert H.rel_l2_rows(v_alone[c], val1[c][lo:hi]).max() <= 1e-2
+    say("small bf16 causality: a prefix gives the same states")
+    wl2 = synth.small_workload(wl.model, [100], wl.commit_layers)
+    v_pre, _, _ = H.run_commit(ctx, wl2, x[lo:lo + 100], "prefill")
+    for c in range(len(wl.commit_layers)):
+        assert H.rel_l2_rows(v_pre[c], val1[c][lo:lo + 100]).max() <= 1e-2
+
+
+def test_edge_cases_and_error_paths(small_bf16):
+    ctx, om, wl, x = small_bf16
+    m = wl.model
+    say("edge: empty batch")
+    wl0 = synth.small_workload(m, [], [1])
+    flags, _, sm = H.run_verify(ctx, wl0, np.zeros(0, np.int32), np.zeros((1, 0, m.d_model), np.uint16), None)
+    assert len(flags) == 0 and sm["n_tokens"] == 0
+    say("edge: no committed layers, token check only")
+    wl_tok = synth.small_workload(m, [50, 20], [], tamper_count=4, seed=5)
+    xt = synth.tokens(wl_tok)
+    _, z = O.prefill(om, xt, wl_tok.lengths, [])
+    check_verify_against_oracle(ctx, om, wl_tok, xt, np.zeros((0, 70, m.d_model), np.float32), z, 2e-2, 5e-2, 0.1)
+    say("edge: hidden only, no token check; NaN / Inf commitments and an invalid token id reject, nothing crashes")
+    wl_h = synth.small_workload(m, [40, 30], [2], check_argmax=False, tamper_count=0, seed=6)
+    xh = synth.tokens(wl_h)
+    hid, _ = O.prefill(om, xh, wl_h.lengths, [2], want_logits=False)
+    com = hid[2][None].astype(np.float32).copy()
+    com[0, 5, 7] = np.nan
+    com[0, 9, 0] = np.inf
+    st = H.stored(com, "bf16")
+    xbad = xh.copy()
+    xbad[69] = m.vocab + 5                  # last token of the second sequence: affects only itself
+    flags, stats, sm = H.run_verify(ctx, wl_h, xbad, st, None)
+    expect = np.ones(70, np.uint8)
+    expect[[5, 9, 69]] = 0
+    np.testing.assert_array_equal(flags, expect)
+    assert np.isnan(stats[0]["max_abs"][5]) and sm["n_rejected"] == 3
+    ref = O.compare_hidden(hid[2], st[0], wl_h.tol_rel_l2, wl_h.tol_max_abs)
+    np.testing.assert_array_equal(ref["ok"][:69], expect[:69].astype(bool))
+    say("errors: capacity, bad layer list, null pointers")
+    d_tok = H.to_dev(np.zeros(2000, np.int32))
+    d_flags = torch.zeros(2000, dtype=torch.uint8, device=H.DEV)
+    tol = P.Tol(0.1, math.inf, 0.25)
+    for lengths, layers, code in [([2000], [1], -3), ([10] * 9, [1], -3), ([600], [1], -3), ([10], [0], -1),
+                                  ([10], [2, 1], -1), ([10], [4], -1), ([-1], [1], -1)]:
+        with pytest.raises(P.VerilLMError) as e:
+            ctx.vl_verify_prefill(d_tok.data_ptr(), lengths, layers, d_tok.data_ptr(), P.VL_BF16, 0, tol, d_flags.data_ptr())
+        assert e.value.code == code, (lengths, layers)
+    with pytest.raises(P.VerilLMError) as e:
+        ctx.vl_verify_prefill(d_tok.data_ptr(), [10], [1], 0, P.VL_BF16, 0, tol, d_flags.data_ptr())
+    assert e.value.code == -1
+    with pytest.raises(P.VerilLMError) as e:
+        ctx.vl_get_logits(0, 5, d_tok.data_ptr())          # the last successful call ran no LM head
+    assert e.value.code == -1
+    say("errors: compute before the weights are loaded")
+    ctx2 = P.Context(H.c_cfg(m, 64, 2, 64), 0, 0)
+    try:
+        w = np.ascontiguousarray(synth.weight(m, synth.WQ, 0))
+        ctx2.vl_load_weights(synth.WQ, 0, w.ctypes.data, w.nbytes)
+        with pytest.raises(P.VerilLMError) as e:
+            ctx2.vl_load_weights(synth.WQ, 0, w.ctypes.data, w.nbytes - 2)
+        assert e.value.code == -1
+        with pytest.raises(P.VerilLMError) as e:
+            ctx2.vl_load_weights(synth.WQ, 7, w.ctypes.data, w.nbytes)
+        assert e.value.code == -1
+        with pytest.raises(P.VerilLMError) as e:
+            ctx2.vl_verify_prefill(d_tok.data_ptr(), [10], [1], d_tok.data_ptr(), P.VL_BF16, 0, tol, d_flags.data_ptr())
+        assert e.value.code == -2
+    finally:
+        ctx2.close()

@@ -1,0 +1,202 @@
+"""GPU parity of the single operations, called through the C ABI, against the CPU oracle."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_24257_amd as P
+import synth
+from oracle import verillm_oracle as O
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx_small_bf16():
+    m = synth.small_model("bf16")
+    ctx = H.make_ctx(m, 2048, 16, 1024)
+    yield ctx, m
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def ctx_hd128():
+    m = synth.small_model("bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, d_model=512, d_ffn=1024, n_layers=1,
+                          vocab=1000, seed=78)
+    ctx = H.make_ctx(m, 4096, 16, 2048)
+    yield ctx, m
+    ctx.close()
+
+
+# ------------------------------------------------------------------ compare kernel (Section 5.7)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 3, 130, 1027])
+def test_compare_matches_oracle(ctx_small_bf16, dtype, n):
+    ctx, m = ctx_small_bf16
+    d = m.d_model
+    say(f"compare dtype={dtype} n={n} d={d}")
+    rng = np.random.default_rng(n)
+    h = (rng.standard_normal((n, d)) * 3).astype(np.float32)
+    star = (h + 0.01 * rng.standard_normal((n, d))).astype(np.float32)
+    if n >= 3:
+        star[1] += 2.0 * rng.standard_normal(d).astype(np.float32)   # tampered row
+        star[2, 5] = np.nan
+    if n > 100:
+        star[7, 3] = np.inf
+        star[9] = 0.0
+        h[11] = 0.0
+        star[11] = 0.0                                                # 0/0 guarded by the tiny denominator
+    st = H.stored(star, dtype)
+    tol = P.Tol(0.05, math.inf, 0.0)
+    d_h, d_s = H.to_dev(h), H.to_dev(st)
+    d_stats = torch.zeros(n * 4, dtype=torch.float32, device=H.DEV)
+    d_ok = torch.full((n,), 9, dtype=torch.uint8, device=H.DEV)
+    ctx.vl_op_compare(d_h.data_ptr(), d_s.data_ptr(), H.hidden_dtype_code(dtype), n, tol, d_stats.data_ptr(), d_ok.data_ptr())
+    got = H.stats_from_dev(d_stats)
+    ref = O.compare_hidden(h, st, 0.05, math.inf)
+    np.testing.assert_array_equal(d_ok.cpu().numpy().astype(bool), ref["ok"])
+    fin = np.isfinite(ref["rel_l2"])
+    for k in ("rel_l2", "max_abs", "mean_abs"):
+        np.testing.assert_allclose(got[k][fin], ref[k][fin], rtol=2e-5, atol=1e-7)
+    np.testing.assert_allclose(got["mean_signed"][fin], ref["mean_signed"][fin], rtol=1e-3, atol=2e-6)
+    assert np.isnan(got["max_abs"][~np.isfinite(ref["max_abs"]) & np.isnan(ref["max_abs"])]).all()
+
+
+def test_compare_is_bit_reproducible(ctx_small_bf16):
+    ctx, m = ctx_small_bf16
+    n, d = 777, m.d_model
+    say("compare reproducibility")
+    rng = np.random.default_rng(0)
+    h = rng.standard_normal((n, d)).astype(np.float32)
+    st = synth.f32_to_bf16_bits(h + 0.1 * rng.standard_normal((n, d)).astype(np.float32))
+    d_h, d_s = H.to_dev(h), H.to_dev(st)
+    outs = []
+    for _ in range(3):
+        d_stats = torch.zeros(n * 4, dtype=torch.float32, device=H.DEV)
+        d_ok = torch.zeros(n, dtype=torch.uint8, device=H.DEV)
+        ctx.vl_op_compare(d_h.data_ptr(), d_s.data_ptr(), P.VL_BF16, n, P.Tol(0.1, math.inf, 0), d_stats.data_ptr(), d_ok.data_ptr())
+        outs.append(d_stats.cpu().numpy().tobytes())
+    assert outs[0] == outs[1] == outs[2]
+
+
+# ------------------------------------------------------------------ argmax + TokenMatch
+@pytest.mark.parametrize("vocab,n", [(1000, 37), (4096, 5), (128256, 9), (1001, 4)])
+def test_argmax_and_token_check_match_oracle(vocab, n):
+    say(f"argmax vocab={vocab} n={n}")
+    m = synth.small_model("f32", vocab=vocab, n_layers=1)
+    ctx = P.Context(H.c_cfg(m, 64, 4, 64), 0, 0)          # op calls need no weights
+    try:
+        rng = np.random.default_rng(vocab + n)
+        z = rng.standard_normal((n, vocab)).astype(np.float32)
+        z[0, 17] = z[0, 400] = z[0].max() + 1.0           # exact tie: lowest index wins
+        z[1, vocab - 1] = 50.0                            # maximum in the very last column
+        z[2, 0] = 60.0
+        a_true = np.argmax(z, axis=1)
+        cam = a_true.astype(np.int32).copy()
+        cam[0] = 400                                      # tied token: gap 0 passes at margin 0
+        cam[1] = 3                                        # wrong token
+        cam[2] = -1                                       # skipped
+        cam[3] = vocab                                    # out of range
+        margin = 0.0
+        d_z, d_c = H.to_dev(z), H.to_dev(cam)
+        d_a = torch.zeros(n, dtype=torch.int32, device=H.DEV)
+        d_g = torch.zeros(n, dtype=torch.float32, device=H.DEV)
+        d_ok = torch.zeros(n, dtype=torch.uint8, device=H.DEV)
+        ctx.vl_op_argmax(d_z.data_ptr(), n, d_c.data_ptr(), margin, d_a.data_ptr(), d_g.data_ptr(), d_ok.data_ptr())
+        a, gap, ok = O.token_check(z, cam, margin)
+        np.testing.assert_array_equal(d_a.cpu().numpy(), a)
+        np.testing.assert_array_equal(d_ok.cpu().numpy().astype(bool), ok)
+        np.testing.assert_allclose(d_g.cpu().numpy().astype(np.float64), gap, rtol=1e-6, atol=1e-6)   # one fp32 subtraction
+        assert d_a.cpu().numpy()[0] == 17
+        # a positive margin lets a near-tie through
+        cam2 = a_true.astype(np.int32).copy()
+        z2 = z.copy()
+        z2[4, (a_true[4] + 1) % vocab] = z2[4, a_true[4]] - 0.01
+        cam2[4] = (a_true[4] + 1) % vocab
+        d_z2, d_c2 = H.to_dev(z2), H.to_dev(cam2)
+        ctx.vl_op_argmax(d_z2.data_ptr(), n, d_c2.data_ptr(), 0.05, d_a.data_ptr(), d_g.data_ptr(), d_ok.data_ptr())
+        _, _, ok2 = O.token_check(z2, cam2, 0.05)
+        np.testing.assert_array_equal(d_ok.cpu().numpy().astype(bool), ok2)
+        assert ok2[4]
+    finally:
+        ctx.close()
+
+
+# ------------------------------------------------------------------ bf16 matrix-core GEMM
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (300, 200, 128), (1, 1, 64), (1000, 520, 192), (513, 257, 4096),
+                                   (2048, 1536, 512)])
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_gemm_bf16_matches_float64_product(ctx_small_bf16, M, N, K, out_dtype):
+    ctx, _ = ctx_small_bf16
+    say(f"gemm M={M} N={N} K={K} out={out_dtype}")
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    a_bits = synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    w_bits = synth.f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.05).astype(np.float32))
+    ref = O.upcast(a_bits) @ O.upcast(w_bits).T
+    d_a, d_w = H.to_dev(a_bits), H.to_dev(w_bits)
+    if out_dtype == "f32":
+        d_o = torch.full((M, N), 7.0, dtype=torch.float32, device=H.DEV)
+        ctx.vl_op_gemm_bf16(d_a.data_ptr(), d_w.data_ptr(), d_o.data_ptr(), P.VL_F32, M, N, K)
+        got = d_o.cpu().numpy().astype(np.float64)
+        # fp32 accumulation of K products of O(0.05) magnitude: error ~ sqrt(K) * 2^-24 * |terms|
+        tol = 1e-5 * math.sqrt(K) * 0.05 * 4
+    else:
+        d_o = torch.zeros((M, N), dtype=torch.int16, device=H.DEV)
+        ctx.vl_op_gemm_bf16(d_a.data_ptr(), d_w.data_ptr(), d_o.data_ptr(), P.VL_BF16, M, N, K)
+        got = O.upcast(H.bits_from_dev(d_o))
+        tol = None
+    if tol is not None:
+        np.testing.assert_allclose(got, ref, rtol=0, atol=max(tol, 1e-5))
+    else:
+        np.testing.assert_allclose(got, ref, rtol=2 ** -8, atol=1e-5)       # one bf16 rounding of the fp32 sum
+
+
+# ------------------------------------------------------------------ matrix-core causal GQA attention
+def _attention_case(ctx, m, lengths, seed):
+    hq, hkv, hd = m.n_q_heads, m.n_kv_heads, m.head_dim
+    n = sum(lengths)
+    rng = np.random.default_rng(seed)
+    qkv = (rng.standard_normal((n, (hq + 2 * hkv) * hd)) * 1.5).astype(np.float32)
+    bits = synth.f32_to_bf16_bits(qkv)
+    vals = O.upcast(bits)
+    d_qkv = H.to_dev(bits)
+    d_out = torch.zeros((n, hq * hd), dtype=torch.int16, device=H.DEV)
+    ctx.vl_op_attention_bf16(d_qkv.data_ptr(), lengths, d_out.data_ptr())
+    got = O.upcast(H.bits_from_dev(d_out)).reshape(n, hq, hd)
+    lo = 0
+    worst = 0.0
+    for t in lengths:
+        if t == 0:
+            continue
+        blk = vals[lo:lo + t]
+        q = blk[:, : hq * hd].reshape(t, hq, hd)
+        k = blk[:, hq * hd:(hq + hkv) * hd].reshape(t, hkv, hd)
+        v = blk[:, (hq + hkv) * hd:].reshape(t, hkv, hd)
+        ref = O.causal_attention(q, k, v, np.arange(t))
+        err = np.abs(got[lo:lo + t] - ref).max()
+        worst = max(worst, err)
+        lo += t
+    return worst
+
+
+@pytest.mark.parametrize("lengths", [[1], [5, 64, 1, 130], [128], [129, 255, 256, 63], [700], [0, 33, 0, 200]])
+def test_attention_hd64_matches_oracle(ctx_small_bf16, lengths):
+    ctx, m = ctx_small_bf16
+    say(f"attention hd64 lengths={lengths}")
+    # probabilities and outputs are rounded to bf16 (2^-9 relative); values are O(1.5)
+    assert _attention_case(ctx, m, lengths, 1) < 3e-2
+
+
+@pytest.mark.parametrize("lengths", [[3], [200, 77], [1024], [65, 1, 127, 128, 192]])
+def test_attention_hd128_gqa4_matches_oracle(ctx_hd128, lengths):
+    ctx, m = ctx_hd128
+    say(f"attention hd128 lengths={lengths}")
+    assert _attention_case(ctx, m, lengths, 2) < 3e-2
