@@ -88,7 +88,7 @@ def test_compare_is_bit_reproducible(ctx_small_bf16):
 
 
 # ------------------------------------------------------------------ argmax + TokenMatch
-@pytest.mark.parametrize("vocab,n", [(1000, 37), (4096, 5), (128256, 9), (1001, 4)])
+@pytest.mark.parametrize("vocab,n", [(1000, 37), (4096, 5), (128256, 9), (1001, 6)])
 def test_argmax_and_token_check_match_oracle(vocab, n):
     say(f"argmax vocab={vocab} n={n}")
     m = synth.small_model("f32", vocab=vocab, n_layers=1)
