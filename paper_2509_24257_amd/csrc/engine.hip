@@ -276,8 +276,10 @@ bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, bool want_tile
     return true;
 }
 
-void gemm(vl_ctx* c, bool prefill, const void* A, const void* W, int M, int N, int K, int epi, void* out) {
-    if (c->bf16 && prefill) launch_gemm_mfma(A, W, M, N, K, epi, out, c->stream);
+// bf16 models: every GEMM runs on the matrix cores (for the few rows of a decode step the kernel is bound by
+// streaming the weight tiles, which is what a decode step has to do anyway).  fp32 models: vector-ALU GEMM.
+void gemm(vl_ctx* c, const void* A, const void* W, int M, int N, int K, int epi, void* out) {
+    if (c->bf16) launch_gemm_mfma(A, W, M, N, K, epi, out, c->stream);
     else launch_gemm_simple(A, W, c->cfg.dtype, M, N, K, epi, out, (int)c->plan.ib, c->stream);
 }
 
@@ -289,7 +291,7 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
     const int rows = (int)bi.rows;
     hipStream_t s = c->stream;
     { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s); }
-    { StageSpan sp(c, VL_STAGE_QKV_GEMM); gemm(c, true, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv); }
+    { StageSpan sp(c, VL_STAGE_QKV_GEMM); gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv); }
     {
         StageSpan sp(c, VL_STAGE_ROPE);
         launch_rope(c->qkv, m.dtype, bi.pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
@@ -309,10 +311,10 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
                                 m.dtype, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
         }
     }
-    { StageSpan sp(c, VL_STAGE_O_GEMM); gemm(c, true, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid); }
+    { StageSpan sp(c, VL_STAGE_O_GEMM); gemm(c, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid); }
     { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s); }
-    { StageSpan sp(c, VL_STAGE_GATEUP_GEMM); gemm(c, true, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act); }
-    { StageSpan sp(c, VL_STAGE_DOWN_GEMM); gemm(c, true, c->act, w.wd, rows, m.d_model, m.d_ffn, EPI_ADD_RESID, c->resid); }
+    { StageSpan sp(c, VL_STAGE_GATEUP_GEMM); gemm(c, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act); }
+    { StageSpan sp(c, VL_STAGE_DOWN_GEMM); gemm(c, c->act, w.wd, rows, m.d_model, m.d_ffn, EPI_ADD_RESID, c->resid); }
 }
 
 // One decoder block over `rows` single positions, each attending to its sequence's KV cache (decode form).
@@ -323,21 +325,21 @@ void block_decode(vl_ctx* c, int l, int rows, const int32_t* pos, const int32_t*
     hipStream_t s = c->stream;
     const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
     launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s);
-    gemm(c, false, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
+    gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
     launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
     launch_kv_store(c->qkv, m.dtype, c->kcache + lo, c->vcache + lo, cache_row, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
     launch_attn_rowwise(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, m.dtype, rows,
                         m.n_q_heads, m.n_kv_heads, m.head_dim, s);
-    gemm(c, false, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid);
+    gemm(c, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid);
     launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s);
-    gemm(c, false, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act);
-    gemm(c, false, c->act, w.wd, rows, m.d_model, m.d_ffn, EPI_ADD_RESID, c->resid);
+    gemm(c, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act);
+    gemm(c, c->act, w.wd, rows, m.d_model, m.d_ffn, EPI_ADD_RESID, c->resid);
 }
 
-void lm_head_logits(vl_ctx* c, bool prefill, int rows) {
+void lm_head_logits(vl_ctx* c, int rows) {
     const vl_model_cfg& m = c->cfg;
     { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, c->final_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, c->stream); }
-    { StageSpan sp(c, VL_STAGE_LM_GEMM); gemm(c, prefill, c->xn, c->lm_head, rows, m.vocab, m.d_model, EPI_STORE_F32, c->logits); }
+    { StageSpan sp(c, VL_STAGE_LM_GEMM); gemm(c, c->xn, c->lm_head, rows, m.vocab, m.d_model, EPI_STORE_F32, c->logits); }
 }
 
 int check_batch(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,
@@ -428,7 +430,7 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
         }
     }
     if (run_head) {
-        lm_head_logits(c, true, rows);
+        lm_head_logits(c, rows);
         hipEvent_t a = c->events[ev++], b = c->events[ev++];
         HIP_TRY(c, hipEventRecord(a, s));
         {
@@ -727,7 +729,7 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
             emit(l, (int)np, d_src);
         }
         if (out_argmax) {
-            lm_head_logits(c, true, (int)np);
+            lm_head_logits(c, (int)np);
             launch_argmax(c->logits, np, m.vocab, nullptr, 0.f, c->argmax, nullptr, nullptr, s);
             launch_scatter_i32(c->argmax, out_argmax, d_src, np, s);
         }
@@ -741,7 +743,7 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
             emit(l, rows, d_dsrc + o);
         }
         if (out_argmax) {
-            lm_head_logits(c, false, rows);
+            lm_head_logits(c, rows);
             launch_argmax(c->logits, rows, m.vocab, nullptr, 0.f, c->argmax, nullptr, nullptr, s);
             launch_scatter_i32(c->argmax, out_argmax, d_dsrc + o, rows, s);
         }

@@ -1,44 +1,66 @@
 // C[M,N] = A[M,K] * W[N,K]^T in bf16 on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulate.
 //
-// Both operands are K-contiguous, so every global load, LDS store and LDS load is a 16-byte vector of 8
+// Both operands are K-contiguous, so every global load, LDS write and LDS read moves 16-byte vectors of 8
 // consecutive k values - exactly what one lane feeds to the MFMA.
 //
-//   workgroup : 512 lanes = 8 waves, output tile 256 x 256, K stepped by 64
-//   waves     : 2 (M) x 4 (N); each wave owns 128 x 64 = 4 x 2 MFMA blocks of 32x32 -> 128 accumulator VGPRs
-//   LDS       : two stages of (256 + 256) rows x 64 k, row pitch 72 elements (144 B): the 16-byte pad makes
-//               consecutive rows land on different banks for the MFMA operand reads; 144 KB of the CU's 160 KB
-//   pipeline  : the loads of k-tile t+1 are issued into registers before the MFMAs of tile t and written to
-//               the other LDS stage after them; one barrier per k-tile
-//   placement : workgroup ids are dealt round-robin to the 8 XCDs, so ids are remapped such that each XCD
-//               walks its own contiguous run of tiles, 8 M-tiles deep before moving to the next N-tile;
-//               the 32 tiles an XCD has in flight then share A and W panels through that XCD's L2
+//   workgroup : 512 lanes = 8 waves, output tile 256 x 256, K stepped by 32
+//   waves     : two groups of four (one wave of each group on every SIMD); group g owns rows 128 g .. 128 g + 127,
+//               wave w of a group owns columns 64 w .. 64 w + 63 as 4 x 2 MFMA blocks of 32x32 (128 accumulator
+//               VGPRs)
+//   ping-pong : both groups run the same stream, [memory phase | barrier | compute phase | barrier] per k-tile,
+//               but group 1 runs one phase behind group 0 (it takes one extra barrier before the loop, group 0 one
+//               after it).  While one wave of a SIMD issues its 16 MFMAs the other one does its LDS reads and
+//               global loads, so the matrix pipe is handed from wave to wave instead of idling.
+//   LDS       : a ring of 5 slots of 32 KB (= all 160 KB of the CU), slot = (256 + 256) rows x 32 k.  Rows are 64 B,
+//               unpadded; the four 16-byte chunks of row r are XOR-swizzled by (r / 4) % 4 so that the 16 lanes the
+//               LDS serves per clock always hit 16 different 16-byte bank groups (measured: zero bank conflicts).
+//   loads     : global -> LDS directly (global_load_lds_dwordx4, no staging registers).  One such instruction
+//               fills 1 KB = 16 consecutive LDS rows; the swizzle is applied on the global-address side.  The loads
+//               of tile p+4 are issued in the memory phase of tile p into the slot tile p-1 has just left, so every
+//               load has three tile periods to land; "vmcnt(12)" before the barrier of that phase guarantees this
+//               wave's part of tile p+1 is in LDS before anybody reads it.
+//   placement : workgroup ids are dealt round-robin to the 8 XCDs, so ids are remapped such that each XCD walks its
+//               own contiguous run of tiles, 8 M-tiles deep before moving to the next N-tile; the 32 tiles an XCD has
+//               in flight then share A and W panels through that XCD's L2.
 //   MFMA layout (32x32x16): operand lane l carries row (l % 32) and 8 consecutive k of half (l / 32);
-//               result register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l % 32]
+//               result register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l % 32].
+//
+// Epilogues: store as bf16 / store as fp32 / add into the fp32 residual stream / SwiGLU on interleaved gate|up
+// column blocks (W rows alternate 32 gate rows and 32 up rows, so MFMA block j=0 is gate and j=1 is up of the same
+// 32 channels and the product silu(gate)*up never leaves registers).
 #include "common.h"
 #include "kernels.h"
 
 namespace vl {
 
-constexpr int GM_BM = 256, GM_BN = 256, GM_BK = 64;
-constexpr int GM_PITCH = 72;                                // elements per LDS row
+constexpr int GM_BM = 256, GM_BN = 256, GM_BK = 32;
+constexpr int GM_ROWB = 64;                                     // bytes per LDS row (32 bf16)
+constexpr int GM_OPER = 256 * GM_ROWB;                          // 16 KB per operand per slot
+constexpr int GM_SLOT = 2 * GM_OPER;                            // 32 KB
+constexpr int GM_SLOTS = 5;                                     // 160 KB: the whole LDS of a CU
 constexpr int GM_THREADS = 512;
-constexpr int GM_STAGE = (GM_BM + GM_BN) * GM_PITCH;        // elements per stage
-constexpr int GM_LDS_BYTES = 2 * GM_STAGE * 2;
 constexpr int GM_GROUP_M = 8;
 constexpr int GM_XCDS = 8;
+
+#define GM_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define GM_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
+// s_barrier fenced for the instruction scheduler: nothing moves across a phase boundary
+#define GM_BARRIER() do { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_barrier(); __builtin_amdgcn_sched_barrier(0); } while (0)
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+constexpr int GM_WAIT_VM12_LGKM0 = 0x007C;                      // vmcnt(12) lgkmcnt(0)
+constexpr int GM_WAIT_VM0_LGKM0 = 0x0070;                       // vmcnt(0)  lgkmcnt(0)
 
 template <int EPI>
 __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                                                                   int M, int N, int K, void* __restrict__ outp,
                                                                   int tiles_m, int tiles_n) {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    bf16* lds = (bf16*)smem_raw;
+    __shared__ __align__(1024) unsigned char ring[GM_SLOTS * GM_SLOT];
 
     // ---- XCD-aware tile order
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + GM_XCDS - 1) / GM_XCDS;
     const int pid = (blockIdx.x % GM_XCDS) * per_xcd + (blockIdx.x / GM_XCDS);
-    if (pid >= total) return;                               // uniform for the whole workgroup
+    if (pid >= total) return;                                   // uniform for the whole workgroup
     const int group_span = GM_GROUP_M * tiles_n;
     const int group = pid / group_span;
     const int first_m = group * GM_GROUP_M;
@@ -49,37 +71,21 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
     const int m0 = tm * GM_BM, n0 = tn * GM_BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int grp = wave >> 2, wn = wave & 3;
 
-    // ---- global -> LDS staging: lane handles 16-byte chunk (row = id / 8, chunk = id % 8), 4 of A and 4 of W
-    const bf16* ga[4];
-    const bf16* gw[4];
-    int lds_off[4];
+    // ---- direct-to-LDS sources.  Load i (0,1) of this wave fills LDS rows 16*(wave + 8 i) .. +15 of an operand:
+    // lane -> (row = 16*(wave + 8 i) + lane/4, physical chunk = lane%4), which must hold logical chunk
+    // phys ^ ((row/4)%4).  Rows past the matrix edge re-read the last row (their results are never stored).
+    const bf16* ga[2];
+    const bf16* gw[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int id = tid + GM_THREADS * i;
-        const int row = id >> 3, c = id & 7;
-        ga[i] = A + (int64_t)min(m0 + row, M - 1) * K + c * 8;      // rows past the edge re-read the last row
+    for (int i = 0; i < 2; ++i) {
+        const int row = 16 * (wave + 8 * i) + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        ga[i] = A + (int64_t)min(m0 + row, M - 1) * K + c * 8;
         gw[i] = W + (int64_t)min(n0 + row, N - 1) * K + c * 8;
-        lds_off[i] = row * GM_PITCH + c * 8;
     }
-    uint4 ra[4], rw[4];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ra[i] = *(const uint4*)(ga[i] + kt * GM_BK);
-            rw[i] = *(const uint4*)(gw[i] + kt * GM_BK);
-        }
-    };
-    auto lstore = [&](int stage) {
-        bf16* as = lds + stage * GM_STAGE;
-        bf16* ws = as + GM_BM * GM_PITCH;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(uint4*)(as + lds_off[i]) = ra[i];
-            *(uint4*)(ws + lds_off[i]) = rw[i];
-        }
-    };
+    const int dma_off = wave * 1024;                            // + i * 8192, + GM_OPER for W
 
     f32x16 acc[4][2];
 #pragma unroll
@@ -89,46 +95,80 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int frag_row = lane & 31, frag_half = lane >> 5;
-    const int a_base = (wm * 128 + frag_row) * GM_PITCH + frag_half * 8;
-    const int w_base = (wn * 64 + frag_row) * GM_PITCH + frag_half * 8;
-
+    // ---- MFMA operand reads: lane (row fr, half fh) reads logical chunk 2s + fh of rows fr + 32 i
+    const int fr = lane & 31, fh = lane >> 5;
+    const int sw = (fr >> 2) & 3;                               // (row/4)%4 is the same for rows fr + 32 i
+    int a_off[2], w_off[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const int phys = (2 * s + fh) ^ sw;
+        a_off[s] = (grp * 128 + fr) * GM_ROWB + phys * 16;
+        w_off[s] = GM_OPER + (wn * 64 + fr) * GM_ROWB + phys * 16;
+    }
     const int KT = K / GM_BK;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) gload(kt + 1);
-        const bf16* as = lds + cur * GM_STAGE;
-        const bf16* ws = as + GM_BM * GM_PITCH;
+
+#define GM_DMA_TILE(SLOT, KTILE)                                                                              \
+    {                                                                                                         \
+        unsigned char* dst_ = ring + (SLOT) * GM_SLOT + dma_off;                                              \
+        __builtin_amdgcn_global_load_lds(GM_GLB(ga[0] + (KTILE) * GM_BK), GM_LDS(dst_), 16, 0, 0);            \
+        __builtin_amdgcn_global_load_lds(GM_GLB(gw[0] + (KTILE) * GM_BK), GM_LDS(dst_ + GM_OPER), 16, 0, 0);  \
+        __builtin_amdgcn_global_load_lds(GM_GLB(ga[1] + (KTILE) * GM_BK), GM_LDS(dst_ + 8192), 16, 0, 0);     \
+        __builtin_amdgcn_global_load_lds(GM_GLB(gw[1] + (KTILE) * GM_BK), GM_LDS(dst_ + GM_OPER + 8192), 16, 0, 0); \
+    }
+
+    // ---- prologue: tiles 0 .. 3 into slots 0 .. 3, everything landed and published
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            bf16x8 af[4], wf[2];
+    for (int p = 0; p < GM_SLOTS - 1; ++p)
+        if (p < KT) GM_DMA_TILE(p, p)
+    __builtin_amdgcn_s_waitcnt(GM_WAIT_VM0_LGKM0);
+    GM_BARRIER();
+    if (grp == 1) GM_BARRIER();                                 // group 1 runs one phase behind group 0
+
+    bf16x8 af[2][4], wf[2][2];
+    int slot_rd = 0, slot_wr = GM_SLOTS - 1;
+    for (int p = 0; p < KT; ++p) {
+        // ---- memory phase: MFMA operands of tile p
+        const unsigned char* base = ring + slot_rd * GM_SLOT;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8*)(as + a_base + i * 32 * GM_PITCH + s * 16);
+        for (int s = 0; s < 2; ++s) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) wf[j] = *(const bf16x8*)(ws + w_base + j * 32 * GM_PITCH + s * 16);
+            for (int i = 0; i < 4; ++i) af[s][i] = *(const bf16x8*)(base + a_off[s] + i * 32 * GM_ROWB);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) wf[s][j] = *(const bf16x8*)(base + w_off[s] + j * 32 * GM_ROWB);
+        }
+        // the loads of tile p+4 go out while those reads are in flight; their slot held tile p-1, which the other
+        // group finished reading before the barrier that ended its previous memory phase
+        const bool more = p + GM_SLOTS - 1 < KT;
+        if (more) GM_DMA_TILE(slot_wr, p + GM_SLOTS - 1)
+        // this wave has issued tiles <= p+4, four loads each: at most three tiles may remain in flight, so that its
+        // part of tile p+1 has landed before the barrier below publishes it
+        if (more) __builtin_amdgcn_s_waitcnt(GM_WAIT_VM12_LGKM0);
+        else __builtin_amdgcn_s_waitcnt(GM_WAIT_VM0_LGKM0);
+        GM_BARRIER();
+        // ---- compute phase
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT) lstore(cur ^ 1);
-        __syncthreads();
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][i], wf[s][j], acc[i][j], 0, 0, 0);
+        GM_BARRIER();
+        slot_rd = slot_rd + 1 == GM_SLOTS ? 0 : slot_rd + 1;
+        slot_wr = slot_wr + 1 == GM_SLOTS ? 0 : slot_wr + 1;
     }
+    if (grp == 0) GM_BARRIER();                                 // every wave has passed the same number of barriers
+#undef GM_DMA_TILE
 
     // ---- epilogue.  Lane l of a 32x32 block holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4.
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int mb = m0 + wm * 128 + i * 32 + row_half;
+        const int mb = m0 + grp * 128 + i * 32 + row_half;
         if (EPI == EPI_SWIGLU) {
-            // W rows alternate 32 gate rows / 32 up rows, so block j=0 is gate and j=1 is up of the same 32 channels
             const int F = N >> 1;
-            const int f = ((n0 + wn * 64) >> 1) + col_in;
             bf16* out = (bf16*)outp;
+            const int f = ((n0 + wn * 64) >> 1) + col_in;
             if (f < F) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -160,15 +200,10 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 
 template <int EPI>
 static void launch_one(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS_BYTES);
-        attr_set = true;
-    }
     const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (N + GM_BN - 1) / GM_BN;
     const int total = tiles_m * tiles_n;
     const int grid = ((total + GM_XCDS - 1) / GM_XCDS) * GM_XCDS;
-    gemm_mfma_kernel<EPI><<<dim3((unsigned)grid), GM_THREADS, GM_LDS_BYTES, s>>>(A, W, M, N, K, out, tiles_m, tiles_n);
+    gemm_mfma_kernel<EPI><<<dim3((unsigned)grid), GM_THREADS, 0, s>>>(A, W, M, N, K, out, tiles_m, tiles_n);
 }
 
 void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s) {
