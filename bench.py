@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="commitments from vl_prefill_commit instead of vl_decode_commit")
     ap.add_argument("--cpu-sample-tokens", type=int, default=64)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, a reference of known size for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -125,6 +127,13 @@ def main():
         return ctx.vl_verify_prefill(d_tok.data_ptr(), wl.lengths, wl.commit_layers, d_com.data_ptr(), hd_code, cam_ptr, tol,
                                      d_flags.data_ptr())
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # the runtime's device-to-device copy: reads 1 GiB, writes 1 GiB
+        torch.mul(src, 1.0, out=dst)        # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         sm = step()
     expect = np.ones(n, np.uint8)
