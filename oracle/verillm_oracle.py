@@ -30,6 +30,15 @@ following norm, for every l including the last.
 Readings that go beyond the paper (per-token relative L2 and max-abs instead of one verdict per
 segment; a logit margin for near-tied argmax) are documented where they are implemented.
 
+Precision.  By default nothing is rounded: float64 throughout.  The paper does not fix a compute
+precision; the bf16 evaluation shapes do ("bf16" = every matrix-product operand is a bf16 value).
+`Model(..., operand_dtype="bf16")` states that reading: the normalised activations, the projected
+q/k/v (again after the rotary embedding), the softmax numerators entering the value product, the
+attention output and the SwiGLU output are each rounded to bf16 (nearest, ties to even) where they
+become an operand of the next matrix product; all sums, norms and softmax statistics stay float64.
+It changes no formula and no order, only inserts roundings, and it exists so that a bf16
+implementation can be checked far more tightly than against the unrounded model.
+
 Pins: every function below is pinned by tests/test_oracle_*.py against closed forms, invariants
 (token-by-token decode equals prefill; causality; batch independence), library routines
 (torch's scaled_dot_product_attention, rms_norm, silu; the `transformers` Llama model on a tiny
@@ -62,6 +71,16 @@ def upcast(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     return a.astype(np.float64)
+
+
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Round to the nearest bf16 value (ties to even) and return it as float64.  Finite inputs only."""
+    f = np.ascontiguousarray(a, dtype=np.float64).astype(np.float32)       # float64 -> float32 is itself nearest-even
+    # a double rounding float64 -> float32 -> bf16 can differ from a direct one only when the float32 result lands
+    # exactly on a bf16 tie, i.e. for a 2^-16 fraction of inputs, by one bf16 ulp: far below every tolerance used
+    u = f.view(np.uint32)
+    r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)
 
 
 # ------------------------------------------------------------------------------------------------
@@ -103,12 +122,14 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     return e / np.sum(e, axis=-1, keepdims=True)
 
 
-def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_positions: np.ndarray) -> np.ndarray:
+def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_positions: np.ndarray,
+                     round_probs=None) -> np.ndarray:
     """Grouped-query causal attention for one sequence.
 
     q [Tq, Hq, hd]; k, v [Tk, Hkv, hd] hold keys/values of positions 0..Tk-1; query row r sits at
     position q_positions[r] and attends to keys j <= q_positions[r].  Q head j uses KV head
-    j // (Hq / Hkv).  Scores are scaled by 1/sqrt(hd).
+    j // (Hq / Hkv).  Scores are scaled by 1/sqrt(hd).  `round_probs`, if given, is applied to the softmax
+    numerators exp(s - max) that multiply the values; the normaliser is the sum of the unrounded numerators.
     """
     tq, hq, hd = q.shape
     tk, hkv, _ = k.shape
@@ -121,8 +142,11 @@ def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_positions: n
         g = j // group
         s = (q[:, j, :] @ k[:, g, :].T) * scale
         s = np.where(allowed, s, -np.inf)
-        p = softmax_rows(s)
-        out[:, j, :] = p @ v[:, g, :]
+        if round_probs is None:
+            out[:, j, :] = softmax_rows(s) @ v[:, g, :]
+        else:
+            e = np.exp(s - np.max(s, axis=-1, keepdims=True))
+            out[:, j, :] = (round_probs(e) @ v[:, g, :]) / np.sum(e, axis=-1, keepdims=True)
     return out
 
 
@@ -143,10 +167,17 @@ class Model:
     """Shape + weight source.  `weights(kind, layer0)` returns the stored tensor; it is upcast here."""
 
     def __init__(self, n_layers: int, d_model: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
-                 d_ffn: int, vocab: int, rms_eps: float, rope_base: float, weights: WeightFn):
+                 d_ffn: int, vocab: int, rms_eps: float, rope_base: float, weights: WeightFn,
+                 operand_dtype: Optional[str] = None):
         self.L, self.d, self.hq, self.hkv, self.hd = n_layers, d_model, n_q_heads, n_kv_heads, head_dim
         self.f, self.v, self.eps, self.base = d_ffn, vocab, float(rms_eps), float(rope_base)
         self._w = weights
+        assert operand_dtype in (None, "bf16")
+        self.operand_dtype = operand_dtype
+
+    def rnd(self, a: np.ndarray) -> np.ndarray:
+        """Rounding applied where a tensor becomes a matrix-product operand (identity unless operand_dtype is set)."""
+        return round_bf16(a) if self.operand_dtype == "bf16" else a
 
     def w(self, kind: int, layer: int = 0) -> np.ndarray:
         return upcast(self._w(kind, layer))
@@ -163,26 +194,27 @@ def _block(m: Model, w: Dict[int, np.ndarray], h: np.ndarray, positions: np.ndar
     Returns (new h, keys, values) with keys/values covering positions 0..max(positions).
     """
     t = h.shape[0]
-    u = rmsnorm(h, w[ATTN_NORM], m.eps)
-    q = (u @ w[WQ].T).reshape(t, m.hq, m.hd)
-    k = (u @ w[WK].T).reshape(t, m.hkv, m.hd)
-    v = (u @ w[WV].T).reshape(t, m.hkv, m.hd)
-    q = apply_rope(q, positions, m.base)
-    k = apply_rope(k, positions, m.base)
+    u = m.rnd(rmsnorm(h, w[ATTN_NORM], m.eps))
+    q = m.rnd(u @ w[WQ].T).reshape(t, m.hq, m.hd)
+    k = m.rnd(u @ w[WK].T).reshape(t, m.hkv, m.hd)
+    v = m.rnd(u @ w[WV].T).reshape(t, m.hkv, m.hd)
+    q = m.rnd(apply_rope(q, positions, m.base))
+    k = m.rnd(apply_rope(k, positions, m.base))
     if k_all is not None:
         k = np.concatenate([k_all, k], axis=0)
         v = np.concatenate([v_all, v], axis=0)
-    o = causal_attention(q, k, v, positions).reshape(t, m.hq * m.hd)
+    o = causal_attention(q, k, v, positions, round_probs=m.rnd if m.operand_dtype else None)
+    o = m.rnd(o).reshape(t, m.hq * m.hd)
     h1 = h + o @ w[WO].T
-    x = rmsnorm(h1, w[FFN_NORM], m.eps)
-    act = silu(x @ w[W_GATE].T) * (x @ w[W_UP].T)
+    x = m.rnd(rmsnorm(h1, w[FFN_NORM], m.eps))
+    act = m.rnd(silu(x @ w[W_GATE].T) * (x @ w[W_UP].T))
     h2 = h1 + act @ w[W_DOWN].T
     return h2, k, v
 
 
 def lm_head(m: Model, h_last: np.ndarray) -> np.ndarray:
     """Decode head: logits = RMSNorm(h^L; g_final) @ W_lm^T."""
-    return rmsnorm(h_last, m.w(FINAL_NORM), m.eps) @ m.w(LM_HEAD).T
+    return m.rnd(rmsnorm(h_last, m.w(FINAL_NORM), m.eps)) @ m.w(LM_HEAD).T
 
 
 def prefill(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: Sequence[int],

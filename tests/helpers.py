@@ -46,16 +46,18 @@ def make_ctx(m: synth.ModelCfg, max_tokens: int, max_seqs: int, max_seq_len: int
     return ctx
 
 
-def oracle_model(m: synth.ModelCfg, override=None) -> O.Model:
+def oracle_model(m: synth.ModelCfg, override=None, progress: str = "", operand_dtype=None) -> O.Model:
     override = override or {}
 
     def w(kind, layer):
+        if progress and kind == synth.ATTN_NORM and layer % 8 == 0:
+            print("[oracle %s] layer %d/%d" % (progress, layer, m.n_layers), flush=True)
         if (kind, layer) in override:
             return override[(kind, layer)]
-        return synth.weight(m, kind, layer, 8)
+        return synth.weight(m, kind, layer, 16)
 
     return O.Model(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab, m.rms_eps,
-                   m.rope_base, w)
+                   m.rope_base, w, operand_dtype=operand_dtype)
 
 
 def to_dev(a: np.ndarray) -> torch.Tensor:

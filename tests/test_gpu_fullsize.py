@@ -1,0 +1,232 @@
+"""Parity at the full evaluation sizes (workloads 1-4: 8B-shape x3, 70B-shape), in the launch configuration
+bench.py times.
+
+The oracle cannot run these shapes whole (125 TFLOP .. 1.2 PFLOP in float64), so:
+  * sampled outputs: by causality the first P positions of a sequence depend on its first P tokens only, and
+    sequences never interact, so the oracle computes a P-token prefix of one sequence exactly (all layers, LM head)
+    and every GPU value at those packed rows is compared with it (tolerances derived from the bf16 format, see
+    sampled_check), flags and statistics of vl_verify_prefill against the oracle's comparator on the same
+    commitments (oracle states + tamper), bit-exact flags;
+  * properties that hold at any size, on ALL positions: flags equal the planted tamper mask when the other rows'
+    commitments are the library's own states; a sequence's states do not depend on what else is in the batch;
+    results are bit-reproducible;
+  * long context (9216): the attention kernel alone is compared with the oracle's attention on sampled query rows
+    over all 9216 keys.
+"""
+import math
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_24257_amd as P
+import synth
+from oracle import verillm_oracle as O
+from tests import helpers as H
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx_8b():
+    m = synth.LLAMA8B
+    say("loading 8B-shape weights")
+    t0 = time.time()
+    ctx = H.make_ctx(m, 18432, 64, 9216)
+    say("8B-shape weights loaded in %.1f s" % (time.time() - t0))
+    yield ctx
+    ctx.close()
+
+
+def sampled_check(ctx, wl, seq, prefix, extra_tamper=3):
+    m = wl.model
+    n, c = wl.n_tokens, len(wl.commit_layers)
+    x = synth.tokens(wl)
+    cu = synth.cu_seqlens(wl.lengths)
+    lo = int(cu[seq])
+    prefix = min(prefix, wl.lengths[seq])
+    rows = np.arange(lo, lo + prefix)
+
+    say(f"{wl.name}: GPU vl_prefill_commit over N={n}")
+    val, st, amax = H.run_commit(ctx, wl, x, "prefill", want_argmax=True)
+
+    say(f"{wl.name}: oracle (exact, then with bf16 operands) on the first {prefix} tokens of sequence {seq}")
+    t0 = time.time()
+    hid, z = O.prefill(H.oracle_model(m, progress=wl.name), x[lo:lo + prefix], [prefix], wl.commit_layers, want_logits=True)
+    hidr, zr = O.prefill(H.oracle_model(m, progress=wl.name + "/bf16", operand_dtype="bf16"), x[lo:lo + prefix], [prefix],
+                         wl.commit_layers, want_logits=True)
+    say(f"{wl.name}: oracle took {time.time() - t0:.1f} s")
+
+    # ---- values.  bf16 keeps 8 significant bits (2^-8 per rounding) and a random-weight network carries each
+    # layer's rounding noise forward, so the distance to the UNROUNDED model grows like sqrt(layer): the exact-
+    # arithmetic model with bf16 operands is itself 7.6e-3 (layer 1) .. 3.8e-2 (layer 32) away from it at the 8B
+    # shape.  What is asserted: the library is no further from the unrounded model than that ideal bf16 model is
+    # (+15 %), it stays within 1.25e-2 sqrt(l) of the unrounded model and within 0.75e-2 sqrt(l) of the bf16 model.
+    for ci, l in enumerate(wl.commit_layers):
+        r = H.rel_l2_rows(val[ci][rows], hid[l])
+        rf = H.rel_l2_rows(hidr[l], hid[l])
+        rg = H.rel_l2_rows(val[ci][rows], hidr[l])
+        print(f"  layer {l}: rel-L2 gpu-vs-exact mean {r.mean():.2e} max {r.max():.2e} | bf16-model-vs-exact mean {rf.mean():.2e} "
+              f"| gpu-vs-bf16-model mean {rg.mean():.2e} max {rg.max():.2e}", flush=True)
+        assert r.mean() <= 1.15 * rf.mean() + 1e-3
+        assert r.max() <= 1.25e-2 * math.sqrt(l)
+        assert rg.max() <= 0.75e-2 * math.sqrt(l)
+    srt = np.sort(z, axis=1)
+    gap_top2 = srt[:, -1] - srt[:, -2]
+    zg_full = H.get_logits(ctx, lo, lo + prefix, m.vocab)
+    err, err_fmt = np.abs(zg_full - z).max(), np.abs(zr - z).max()
+    print(f"  logits max-abs err: gpu-vs-exact {err:.3e}, bf16-model-vs-exact {err_fmt:.3e}, gpu-vs-bf16-model "
+          f"{np.abs(zg_full - zr).max():.3e}", flush=True)
+    assert err <= 1.25 * err_fmt + 0.02 and err <= 0.6
+    # the argmax kernel itself is exact: it must reproduce the argmax of the logits it was given, over the full vocabulary
+    np.testing.assert_array_equal(amax[rows], np.argmax(zg_full, axis=1))
+    # and agrees with the oracle wherever the oracle's top-2 gap exceeds twice the row's logit error (it must, by
+    # arithmetic), and on most positions with a gap >= 0.1
+    row_err = np.abs(zg_full - z).max(axis=1)
+    clear = gap_top2 >= 2 * row_err + 1e-6
+    np.testing.assert_array_equal(amax[rows][clear], O.argmax_lowest(z)[clear])
+    loose = gap_top2 >= 0.1
+    agree = float((amax[rows][loose] == O.argmax_lowest(z)[loose]).mean()) if loose.any() else 1.0
+    print(f"  argmax agreement where the oracle's top-2 gap >= 0.1: {agree:.4f} ({loose.sum()} positions)", flush=True)
+    assert agree >= 0.9
+
+    # ---- commitments: oracle states on the sampled rows, the library's own states elsewhere; tamper both
+    com = val.copy()
+    for ci, l in enumerate(wl.commit_layers):
+        com[ci][rows] = hid[l].astype(np.float32)
+    cam = amax.copy()
+    cam[rows] = O.argmax_lowest(z).astype(np.int32)
+    pos = synth.tamper_positions(wl)
+    inside = rows[np.random.default_rng(wl.tamper_seed).choice(prefix, size=min(extra_tamper, prefix), replace=False)]
+    pos = np.unique(np.concatenate([pos, inside]))
+    com_t = synth.tamper_hidden(wl, com, pos)
+    wrong = cam.copy()
+    wrong[rows] = np.argmin(z, axis=1)                     # on sampled rows: the token with the smallest oracle logit
+    other = np.setdiff1d(np.arange(n), rows)
+    wrong[other] = (cam[other] + 1 + (np.arange(len(other)) * 7919) % (m.vocab - 1)) % m.vocab
+    cam_t, changed = synth.tamper_argmax(wl, cam, pos, wrong_tokens=wrong)
+    com_st = H.stored(com_t, wl.hidden_dtype)
+
+    say(f"{wl.name}: GPU vl_verify_prefill")
+    flags, stats, sm = H.run_verify(ctx, wl, x, com_st, cam_t if wl.check_argmax else None)
+    print(f"  verify: {sm['ms_forward']:.1f} ms, compare part {sm['ms_compare']:.2f} ms, rejected {sm['n_rejected']}", flush=True)
+    expect = np.ones(n, np.uint8)
+    expect[pos] = 0
+    np.testing.assert_array_equal(flags, expect)                          # all N positions against the planted mask
+    # oracle comparator on the sampled rows, same commitments
+    ref_stats = [O.compare_hidden(hid[l], com_st[ci][rows], wl.tol_rel_l2, wl.tol_max_abs) for ci, l in enumerate(wl.commit_layers)]
+    if wl.check_argmax:
+        _, ref_gap, ref_tok = O.token_check(z, cam_t[rows], wl.tol_logit_margin)
+    else:
+        ref_gap, ref_tok = None, None
+    ref_flags = O.flags([s["ok"] for s in ref_stats], ref_tok)
+    np.testing.assert_array_equal(flags[rows], ref_flags)                 # bit-exact against the oracle
+    for ci in range(c):
+        assert np.abs(stats[ci]["rel_l2"][rows] - ref_stats[ci]["rel_l2"]).max() <= 1.25e-2 * math.sqrt(wl.commit_layers[ci]) * 1.5
+        honest = ~np.isin(rows, pos)
+        # honest rows here carry the UNROUNDED model's states: the bf16 format noise against them (5.6e-2 at layer 32)
+        # must stay clear of the acceptance tolerance; two bf16 runs are much closer (see the decode test)
+        assert stats[ci]["rel_l2"][rows][honest].max() <= 0.75 * wl.tol_rel_l2
+    if wl.check_argmax:
+        _, gap_gpu = H.get_argmax(ctx, lo, lo + prefix)
+        fin = np.isfinite(ref_gap)
+        assert np.abs(gap_gpu[fin] - ref_gap[fin]).max() <= 2 * err + 1e-3
+    assert sm["n_rejected"] == len(pos)
+    return val, st, amax, x
+
+
+def test_workload1_8b_batch8x1024(ctx_8b):
+    wl = synth.workload(1)
+    val, st, amax, x = sampled_check(ctx_8b, wl, seq=3, prefix=96)
+    say("workload 1: bit-reproducible")
+    val2, st2, amax2 = H.run_commit(ctx_8b, wl, x, "prefill")
+    assert st.tobytes() == st2.tobytes() and amax.tobytes() == amax2.tobytes()
+    say("workload 1: a sequence alone gives the states it has inside the batch")
+    cu = synth.cu_seqlens(wl.lengths)
+    wl1 = synth.Workload("one", wl.model, (1024,), (512,), wl.commit_layers, True, "bf16", 0, "rel", 0.1, math.inf, 0.25)
+    v1, _, _ = H.run_commit(ctx_8b, wl1, x[int(cu[5]):int(cu[6])], "prefill")
+    for ci in range(len(wl.commit_layers)):
+        assert H.rel_l2_rows(v1[ci], val[ci][int(cu[5]):int(cu[6])]).max() <= 0.75e-2 * math.sqrt(wl.commit_layers[ci])
+
+
+def test_workload1_decode_commitments_verify_clean(ctx_8b):
+    wl = synth.workload(1)
+    x = synth.tokens(wl)
+    say("workload 1: vl_decode_commit (512-token prompts prefilled, 512 positions token by token)")
+    t0 = time.time()
+    val_d, st_d, amax_d = H.run_commit(ctx_8b, wl, x, "decode", prompt_lens=wl.prompt_lens)
+    say("decode commit took %.1f s" % (time.time() - t0))
+    val_p, _, amax_p = H.run_commit(ctx_8b, wl, x, "prefill")
+    for ci, l in enumerate(wl.commit_layers):
+        r = H.rel_l2_rows(val_d[ci], val_p[ci])
+        print(f"  layer {l}: honest decode-vs-prefill rel-L2 max {r.max():.2e}", flush=True)
+        assert r.max() <= wl.tol_rel_l2 / 2
+    pos = synth.tamper_positions(wl)
+    com_t = synth.tamper_hidden(wl, val_d, pos)
+    cam_t, _ = synth.tamper_argmax(wl, amax_d, pos)
+    flags, _, sm = H.run_verify(ctx_8b, wl, x, H.stored(com_t, "bf16"), cam_t)
+    expect = np.ones(wl.n_tokens, np.uint8)
+    expect[pos] = 0
+    np.testing.assert_array_equal(flags, expect)
+    assert sm["n_rejected"] == len(pos)
+
+
+def test_workload2_8b_varlen64(ctx_8b):
+    wl = synth.workload(2)
+    longest = int(np.argmax(wl.lengths))
+    sampled_check(ctx_8b, wl, seq=longest, prefix=80)
+
+
+def test_workload3_8b_long_context(ctx_8b):
+    wl = synth.workload(3)
+    val, st, amax, x = sampled_check(ctx_8b, wl, seq=1, prefix=64)
+    say("workload 3: the first 1000 positions of a 9216-token sequence equal a 1000-token run (causality)")
+    wl_p = synth.Workload("prefix", wl.model, (1000,), (500,), wl.commit_layers, True, "bf16", 0, "rel", 0.1, math.inf, 0.25)
+    vp, _, _ = H.run_commit(ctx_8b, wl_p, x[9216:9216 + 1000], "prefill")
+    for ci in range(len(wl.commit_layers)):
+        assert H.rel_l2_rows(vp[ci], val[ci][9216:9216 + 1000]).max() <= 0.75e-2 * math.sqrt(wl.commit_layers[ci])
+
+
+def test_long_context_attention_sampled_rows(ctx_8b):
+    m = synth.LLAMA8B
+    hq, hkv, hd = m.n_q_heads, m.n_kv_heads, m.head_dim
+    t = 9216
+    say("attention alone at T=9216, 32/8 heads x 128, sampled query rows against the oracle")
+    rng = np.random.default_rng(9)
+    bits = synth.f32_to_bf16_bits(rng.standard_normal((t, (hq + 2 * hkv) * hd)).astype(np.float32))
+    d_qkv = H.to_dev(bits)
+    d_out = torch.zeros((t, hq * hd), dtype=torch.int16, device=H.DEV)
+    ctx_8b.vl_op_attention_bf16(d_qkv.data_ptr(), [t], d_out.data_ptr())
+    got = O.upcast(H.bits_from_dev(d_out)).reshape(t, hq, hd)
+    qrows = np.array([0, 1, 63, 64, 127, 128, 129, 4095, 4096, 8191, 9000, 9215])
+    vals = O.upcast(bits)
+    q = vals[qrows][:, : hq * hd].reshape(len(qrows), hq, hd)
+    k = vals[:, hq * hd:(hq + hkv) * hd].reshape(t, hkv, hd)
+    v = vals[:, (hq + hkv) * hd:].reshape(t, hkv, hd)
+    heads = [0, 5, 31]                                       # oracle on three query heads (kv heads 0, 1, 7)
+    for j in heads:
+        g = j // (hq // hkv)
+        ref = O.causal_attention(q[:, j:j + 1], k[:, g:g + 1], v[:, g:g + 1], qrows)
+        err = np.abs(got[qrows][:, j] - ref[:, 0]).max()
+        print(f"  head {j}: max-abs err {err:.3e}", flush=True)
+        assert err <= 2e-2
+
+
+def test_workload4_70b_batch4x2048():
+    wl = synth.workload(4)
+    m = wl.model
+    say("loading 70B-shape weights (141 GB)")
+    t0 = time.time()
+    ctx = H.make_ctx(m, wl.n_tokens, len(wl.lengths), max(wl.lengths))
+    say("70B-shape weights loaded in %.1f s" % (time.time() - t0))
+    try:
+        sampled_check(ctx, wl, seq=2, prefix=24)
+    finally:
+        ctx.close()

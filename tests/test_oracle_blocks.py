@@ -175,3 +175,32 @@ def test_upcast_bf16_bits_exact():
     np.testing.assert_array_equal(O.upcast(bits), [1.0, -2.0, 0.10009765625, 0.0])
     f = np.array([1.5, -0.25], dtype=np.float32)
     assert O.upcast(f).dtype == np.float64 and O.upcast(f).tolist() == [1.5, -0.25]
+
+
+# ---------------------------------------------------------------- bf16 operand rounding (the "bf16 model" reading)
+def test_round_bf16_literals_and_ties():
+    # 1 + 2^-8 is an exact tie between 1.0 and 1 + 2^-7: even mantissa wins (1.0); 1 + 3*2^-8 ties up to 1 + 2^-6
+    x = np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 0.1, 3.0e38, 1e-30, 0.0])
+    y = O.round_bf16(x)
+    np.testing.assert_array_equal(y[:4], [1.0, 1.0, 1.015625, -1.0])
+    assert y[4] == 0.10009765625 and y[7] == 0.0
+    assert abs(y[5] - 3.0e38) / 3.0e38 < 2 ** -8 and abs(y[6] - 1e-30) / 1e-30 < 2 ** -8
+    # idempotent, and agrees with torch's conversion
+    z = RNG.standard_normal(50000) * 7
+    r = O.round_bf16(z)
+    np.testing.assert_array_equal(O.round_bf16(r), r)
+    ref = torch.from_numpy(z.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(r, ref)
+    assert (np.abs(r - z) <= np.abs(z) * 2 ** -8).all()
+
+
+def test_attention_with_rounded_numerators_stays_close_and_normalised():
+    t, hq, hkv, hd = 11, 4, 2, 16
+    q = RNG.standard_normal((t, hq, hd))
+    k = RNG.standard_normal((t, hkv, hd))
+    v = np.ones((t, hkv, hd))
+    exact = O.causal_attention(q, k, v, np.arange(t))
+    rounded = O.causal_attention(q, k, v, np.arange(t), round_probs=O.round_bf16)
+    np.testing.assert_allclose(exact, 1.0, rtol=1e-14)            # weights sum to one
+    assert np.abs(rounded - 1.0).max() < 2 ** -8                   # each numerator moved by < 2^-8 relative
+    assert np.abs(rounded - 1.0).max() > 0                         # and the rounding is really applied
