@@ -145,7 +145,8 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
         if (more) __builtin_amdgcn_s_waitcnt(GM_WAIT_VM12_LGKM0);
         else __builtin_amdgcn_s_waitcnt(GM_WAIT_VM0_LGKM0);
         GM_BARRIER();
-        // ---- compute phase
+        // ---- compute phase (raised priority: the MFMAs win issue arbitration over the other wave's memory phase)
+        __builtin_amdgcn_s_setprio(2);
 #pragma unroll
         for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -153,6 +154,7 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][i], wf[s][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
         GM_BARRIER();
         slot_rd = slot_rd + 1 == GM_SLOTS ? 0 : slot_rd + 1;
         slot_wr = slot_wr + 1 == GM_SLOTS ? 0 : slot_wr + 1;
@@ -162,6 +164,46 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 
     // ---- epilogue.  Lane l of a 32x32 block holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4.
     const int col_in = lane & 31, row_half = (lane >> 5) * 4;
+    const bool interior = (m0 + GM_BM <= M) && (n0 + GM_BN <= N);      // uniform: no per-element guards needed
+    if (interior) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int mb = m0 + grp * 128 + i * 32 + row_half;
+            if (EPI == EPI_SWIGLU) {
+                const int F = N >> 1;
+                bf16* out = (bf16*)outp + (int64_t)mb * F + ((n0 + wn * 64) >> 1) + col_in;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float g = acc[i][0][r], u = acc[i][1][r];
+                    out[(int64_t)((r >> 2) * 8 + (r & 3)) * F] = (bf16)(g / (1.0f + __expf(-g)) * u);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int64_t base = (int64_t)mb * N + n0 + wn * 64 + j * 32 + col_in;
+                    if (EPI == EPI_ADD_RESID) {
+                        // all sixteen residual loads of a block go out before the first one is needed
+                        float* out = (float*)outp + base;
+                        float old[16];
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) old[r] = out[(int64_t)((r >> 2) * 8 + (r & 3)) * N];
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) out[(int64_t)((r >> 2) * 8 + (r & 3)) * N] = old[r] + acc[i][j][r];
+                    } else if (EPI == EPI_STORE_F32) {
+                        float* out = (float*)outp + base;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) out[(int64_t)((r >> 2) * 8 + (r & 3)) * N] = acc[i][j][r];
+                    } else {
+                        bf16* out = (bf16*)outp + base;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) out[(int64_t)((r >> 2) * 8 + (r & 3)) * N] = (bf16)acc[i][j][r];
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // edge tiles: the same stores with row and column guards
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int mb = m0 + grp * 128 + i * 32 + row_half;
