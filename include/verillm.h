@@ -158,6 +158,30 @@ int vl_verify_prefill(vl_ctx* ctx,
                       const vl_tol* tol,
                       uint8_t* flags, vl_tok_stats* stats, vl_summary* summary);
 
+/* Section 5.6, segment-local form: the verifier of one layer segment recomputes only blocks start_layer+1 ..
+ * end_layer.  For start_layer > 0 it starts from the states recorded at the upstream boundary (the inferencer's
+ * commitment for layer start_layer, taken as given), so the verifiers of different segments need nothing from
+ * each other; for start_layer == 0 it starts from the token embedding and `upstream_hidden` is ignored.
+ * Everything else is vl_verify_prefill restricted to the segment:
+ *
+ * start_layer, end_layer   0 <= start_layer < end_layer <= n_layers
+ * upstream_hidden  [device] [N][d_model] in `upstream_dtype` (VL_F32 or VL_BF16); upcast exactly to the fp32
+ *                           residual stream.  Required when start_layer > 0.
+ * tokens           [device] int32 [N]; required when start_layer == 0, otherwise unused and may be NULL
+ * commit_layers    [host]   as above, every entry in (start_layer, end_layer]
+ * committed_argmax [device] as above; allowed only when end_layer == n_layers (VL_E_ARG otherwise)
+ * Only the tensors of blocks start_layer+1 .. end_layer (plus the embedding when start_layer == 0, plus the final
+ * norm and LM head when committed_argmax != NULL) must have been loaded; VL_E_WEIGHTS otherwise.
+ * flags / stats / summary as in vl_verify_prefill, stats indexed [c][n] over this call's commit_layers. */
+int vl_verify_segment(vl_ctx* ctx, int32_t start_layer, int32_t end_layer,
+                      const void* upstream_hidden, int32_t upstream_dtype,
+                      const int32_t* tokens, const int32_t* lengths, int32_t B,
+                      const int32_t* commit_layers, int32_t C,
+                      const void* committed_hidden, int32_t hidden_dtype,
+                      const int32_t* committed_argmax,
+                      const vl_tol* tol,
+                      uint8_t* flags, vl_tok_stats* stats, vl_summary* summary);
+
 /* Section 5.6: the same prefill, but RETURNING the states instead of comparing them ("each verifier must
  * return its computed outputs through the same interface as during inference").
  * out_hidden [device] [C][N][d_model] in hidden_dtype, or NULL; out_argmax [device] int32 [N], or NULL

@@ -373,13 +373,26 @@ def summary(stats: Sequence[dict], token_ok: Optional[np.ndarray], flag: np.ndar
 
 def verify(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: Sequence[int],
            committed_hidden: np.ndarray, committed_argmax: Optional[np.ndarray],
-           tol_rel_l2: float, tol_max_abs: float, tol_logit_margin: float):
+           tol_rel_l2: float, tol_max_abs: float, tol_logit_margin: float,
+           start_layer: int = 0, upstream_hidden: Optional[np.ndarray] = None, end_layer: Optional[int] = None):
     """The whole hot path: prefill, compare at every committed layer, token check, flags, summary.
 
     committed_hidden [C, N, d] in stored dtype.  Returns dict with hidden, logits, stats (list over C),
     argmax, gap, token_ok, flags, summary.
+
+    With start_layer > 0 (and/or end_layer < L) this is one verifier of the segment scheme of Section 5.6:
+    it takes the recorded states entering block start_layer+1 as given (upstream_hidden [N, d], stored
+    dtype), recomputes blocks start_layer+1 .. end_layer only and judges the commitments inside that range.
+    The token check belongs to the segment that ends at the last layer.
     """
-    hidden, logits = prefill(m, tokens, lengths, commit_layers, want_logits=committed_argmax is not None)
+    end_layer = m.L if end_layer is None else end_layer
+    assert 0 <= start_layer < end_layer <= m.L
+    assert all(start_layer < l <= end_layer for l in commit_layers)
+    assert committed_argmax is None or end_layer == m.L
+    hidden, logits = prefill(m, tokens, lengths, commit_layers, want_logits=committed_argmax is not None,
+                             start_layer=start_layer,
+                             start_hidden=None if start_layer == 0 else upcast(upstream_hidden),
+                             end_layer=end_layer)
     stats = [compare_hidden(hidden[l], committed_hidden[c], tol_rel_l2, tol_max_abs)
              for c, l in enumerate(commit_layers)]
     if committed_argmax is not None:

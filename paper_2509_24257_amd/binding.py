@@ -15,7 +15,7 @@ VL_OK, VL_E_ARG, VL_E_WEIGHTS, VL_E_CAPACITY, VL_E_HIP, VL_E_NOMEM = 0, -1, -2, 
 _STATUS = {0: "VL_OK", -1: "VL_E_ARG", -2: "VL_E_WEIGHTS", -3: "VL_E_CAPACITY", -4: "VL_E_HIP", -5: "VL_E_NOMEM"}
 
 EXPORTS = ["vl_plan_memory", "vl_create", "vl_load_weights", "vl_destroy", "vl_last_error", "vl_verify_prefill",
-           "vl_prefill_commit", "vl_decode_commit", "vl_get_logits", "vl_get_argmax", "vl_profile_enable",
+           "vl_verify_segment", "vl_prefill_commit", "vl_decode_commit", "vl_get_logits", "vl_get_argmax", "vl_profile_enable",
            "vl_profile_read", "vl_op_gemm_bf16",
            "vl_op_attention_bf16", "vl_op_compare", "vl_op_argmax"]
 
@@ -81,6 +81,8 @@ def load_library():
     lib.vl_last_error.restype = C.c_char_p
     lib.vl_verify_prefill.argtypes = [vp, vp, i32p, C.c_int32, i32p, C.c_int32, vp, C.c_int32, vp, C.POINTER(Tol), vp, vp,
                                       C.POINTER(Summary)]
+    lib.vl_verify_segment.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int32, vp, i32p, C.c_int32, i32p, C.c_int32, vp, C.c_int32,
+                                      vp, C.POINTER(Tol), vp, vp, C.POINTER(Summary)]
     lib.vl_prefill_commit.argtypes = [vp, vp, i32p, C.c_int32, i32p, C.c_int32, vp, C.c_int32, vp]
     lib.vl_decode_commit.argtypes = [vp, vp, i32p, i32p, C.c_int32, i32p, C.c_int32, vp, C.c_int32, vp]
     lib.vl_get_logits.argtypes = [vp, C.c_int64, C.c_int64, vp]
@@ -151,6 +153,19 @@ class Context:
         ca, c = _i32(commit_layers)
         sm = Summary()
         self._check(lib().vl_verify_prefill(self._h, C.c_void_p(tokens or None), la, b, ca, c,
+                                            C.c_void_p(committed_hidden or None), int(hidden_dtype),
+                                            C.c_void_p(committed_argmax or None), C.byref(tol), C.c_void_p(flags or None),
+                                            C.c_void_p(stats or None), C.byref(sm)))
+        return sm
+
+    def vl_verify_segment(self, start_layer: int, end_layer: int, upstream_hidden: int, upstream_dtype: int, tokens: int,
+                          lengths: Sequence[int], commit_layers: Sequence[int], committed_hidden: int, hidden_dtype: int,
+                          committed_argmax: int, tol: Tol, flags: int, stats: int = 0) -> Summary:
+        la, b = _i32(lengths)
+        ca, c = _i32(commit_layers)
+        sm = Summary()
+        self._check(lib().vl_verify_segment(self._h, int(start_layer), int(end_layer), C.c_void_p(upstream_hidden or None),
+                                            int(upstream_dtype), C.c_void_p(tokens or None), la, b, ca, c,
                                             C.c_void_p(committed_hidden or None), int(hidden_dtype),
                                             C.c_void_p(committed_argmax or None), C.byref(tol), C.c_void_p(flags or None),
                                             C.c_void_p(stats or None), C.byref(sm)))

@@ -212,6 +212,17 @@ bool all_loaded(const vl_ctx* c) {
     return true;
 }
 
+// The tensors a pass over blocks lo+1 .. hi touches: those blocks, the embedding if it starts from tokens, the final
+// norm and LM head if it ends with the token check.
+bool range_loaded(const vl_ctx* c, int lo, int hi, bool embed, bool head) {
+    for (int l = lo; l < hi; ++l)
+        for (int k = 0; k < VL_T_COUNT; ++k)
+            if (k != VL_T_EMBED && k != VL_T_FINAL_NORM && k != VL_T_LM_HEAD && !c->loaded[(size_t)l * VL_T_COUNT + k]) return false;
+    if (embed && !c->loaded[VL_T_EMBED]) return false;
+    if (head && (!c->loaded[VL_T_FINAL_NORM] || !c->loaded[VL_T_LM_HEAD])) return false;
+    return true;
+}
+
 struct LayerW { float* attn_norm; char* wqkv; char* wo; float* ffn_norm; char* wgu; char* wd; };
 LayerW layer_w(const vl_ctx* c, int l) {
     char* s = c->layer_slab[l];
@@ -343,7 +354,7 @@ void lm_head_logits(vl_ctx* c, int rows) {
 }
 
 int check_batch(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,
-                int32_t hidden_dtype, int64_t* n_out) {
+                int32_t hidden_dtype, int64_t* n_out, bool whole_model = true) {
     if (!c) return VL_E_ARG;
     if (B < 0 || (B > 0 && !lengths)) return c->fail(VL_E_ARG, "lengths is NULL or B < 0");
     if (C < 0 || (C > 0 && !commit_layers)) return c->fail(VL_E_ARG, "commit_layers is NULL or C < 0");
@@ -361,8 +372,10 @@ int check_batch(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
         if (commit_layers[i] < 1 || commit_layers[i] > c->cfg.n_layers) return c->fail(VL_E_ARG, fmt("commit_layers[%d] = %d outside [1, %d]", i, commit_layers[i], c->cfg.n_layers));
         if (i > 0 && commit_layers[i] <= commit_layers[i - 1]) return c->fail(VL_E_ARG, "commit_layers must be strictly ascending");
     }
-    if (n > 0 && !tokens) return c->fail(VL_E_ARG, "tokens is NULL");
-    if (!all_loaded(c)) return c->fail(VL_E_WEIGHTS, "not every weight tensor has been loaded");
+    if (whole_model) {
+        if (n > 0 && !tokens) return c->fail(VL_E_ARG, "tokens is NULL");
+        if (!all_loaded(c)) return c->fail(VL_E_WEIGHTS, "not every weight tensor has been loaded");
+    }
     *n_out = n;
     return VL_OK;
 }
@@ -372,14 +385,32 @@ int upload_stage(vl_ctx* c, const Stage& st) {
     return VL_OK;
 }
 
+// A pass that covers only blocks start_layer+1 .. end_layer and, for start_layer > 0, begins from recorded states.
+struct Segment { int start_layer, end_layer; const void* upstream_hidden; int upstream_dtype; };
+
 // The shared prefill driver: compare against commitments (verify) or write the states out (commit).
 int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,
                 const void* committed_hidden, void* out_hidden, int32_t hidden_dtype, const int32_t* committed_argmax,
                 int32_t* out_argmax, bool run_head, const vl_tol* tol, uint8_t* flags, vl_tok_stats* stats_out,
-                vl_summary* summary, bool verify) {
+                vl_summary* summary, bool verify, const Segment* seg = nullptr) {
     int64_t n = 0;
-    int rc = check_batch(c, tokens, lengths, B, commit_layers, C, hidden_dtype, &n);
+    int rc = check_batch(c, tokens, lengths, B, commit_layers, C, hidden_dtype, &n, seg == nullptr);
     if (rc) return rc;
+    const int layer_lo = seg ? seg->start_layer : 0, layer_hi = seg ? seg->end_layer : c->cfg.n_layers;
+    const bool from_tokens = !seg || seg->start_layer == 0;
+    if (seg) {
+        if (layer_lo < 0 || layer_hi > c->cfg.n_layers || layer_lo >= layer_hi)
+            return c->fail(VL_E_ARG, fmt("segment (%d, %d] is not a non-empty layer range inside [0, %d]", layer_lo, layer_hi, c->cfg.n_layers));
+        for (int i = 0; i < C; ++i)
+            if (commit_layers[i] <= layer_lo || commit_layers[i] > layer_hi)
+                return c->fail(VL_E_ARG, fmt("commit_layers[%d] = %d outside the segment (%d, %d]", i, commit_layers[i], layer_lo, layer_hi));
+        if (run_head && layer_hi != c->cfg.n_layers) return c->fail(VL_E_ARG, "the token check needs a segment that ends at the last layer");
+        if (seg->upstream_dtype != VL_F32 && seg->upstream_dtype != VL_BF16) return c->fail(VL_E_ARG, "upstream_dtype must be VL_F32 or VL_BF16");
+        if (n > 0 && from_tokens && !tokens) return c->fail(VL_E_ARG, "tokens is NULL for a segment that starts at the embedding");
+        if (n > 0 && !from_tokens && !seg->upstream_hidden) return c->fail(VL_E_ARG, "upstream_hidden is NULL");
+        if (!range_loaded(c, layer_lo, layer_hi, from_tokens, run_head))
+            return c->fail(VL_E_WEIGHTS, "a weight tensor this segment needs has not been loaded");
+    }
     HIP_TRY(c, hipSetDevice(c->device));
     c->last_n = 0;
     c->last_has_logits = false;
@@ -407,9 +438,13 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
         launch_fill_u8(c->hid_ok, 1, n, s);
         launch_fill_u8(c->tok_ok, 1, n, s);
     }
-    { StageSpan sp(c, VL_STAGE_EMBED); launch_embed(c->embed, m.dtype, tokens, nullptr, c->resid, verify ? c->hid_ok : nullptr, nullptr, n, m.d_model, m.vocab, s); }
+    {
+        StageSpan sp(c, VL_STAGE_EMBED);
+        if (from_tokens) launch_embed(c->embed, m.dtype, tokens, nullptr, c->resid, verify ? c->hid_ok : nullptr, nullptr, n, m.d_model, m.vocab, s);
+        else launch_load_hidden(seg->upstream_hidden, seg->upstream_dtype, c->resid, n, m.d_model, s);
+    }
     int ci = 0;
-    for (int l = 0; l < m.n_layers; ++l) {
+    for (int l = layer_lo; l < layer_hi; ++l) {
         block_prefill(c, l, bi, nullptr);
         if (ci < C && commit_layers[ci] == l + 1) {
             const int64_t off = (int64_t)ci * n * m.d_model * (hidden_dtype == VL_BF16 ? 2 : 4);
@@ -645,6 +680,17 @@ int vl_verify_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, 
     if (!tol) return c->fail(VL_E_ARG, "tol is NULL");
     return run_prefill(c, tokens, lengths, B, commit_layers, C, committed_hidden, nullptr, hidden_dtype, committed_argmax, nullptr,
                        committed_argmax != nullptr, tol, flags, stats, summary, true);
+}
+
+int vl_verify_segment(vl_ctx* c, int32_t start_layer, int32_t end_layer, const void* upstream_hidden, int32_t upstream_dtype,
+                      const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,
+                      const void* committed_hidden, int32_t hidden_dtype, const int32_t* committed_argmax, const vl_tol* tol,
+                      uint8_t* flags, vl_tok_stats* stats, vl_summary* summary) {
+    if (!c) return VL_E_ARG;
+    if (!tol) return c->fail(VL_E_ARG, "tol is NULL");
+    const Segment seg{start_layer, end_layer, upstream_hidden, upstream_dtype};
+    return run_prefill(c, tokens, lengths, B, commit_layers, C, committed_hidden, nullptr, hidden_dtype, committed_argmax, nullptr,
+                       committed_argmax != nullptr, tol, flags, stats, summary, true, &seg);
 }
 
 int vl_prefill_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,

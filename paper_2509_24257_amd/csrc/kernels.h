@@ -29,6 +29,7 @@ void launch_transpose_v(const void* qkv, void* vt, const int32_t* vt_col, int64_
 void launch_kv_store(const void* qkv, int dtype, void* kcache, void* vcache, const int32_t* cache_row,
                      int64_t rows, int hq, int hkv, int hd, hipStream_t s);
 // out[(dst ? dst[n] : n), :] = resid[n, :] converted to `dtype`.
+void launch_load_hidden(const void* in, int dtype, float* resid, int64_t rows, int d, hipStream_t s);
 void launch_store_hidden(const float* resid, void* out, int dtype, const int32_t* dst, int64_t rows, int d,
                          hipStream_t s);
 void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, int64_t rows, hipStream_t s);

@@ -192,6 +192,23 @@ void launch_store_hidden(const float* resid, void* out, int dtype, const int32_t
         store_hidden_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(resid, (float*)out, dst, d);
 }
 
+// ---------------------------------------------------------------- recorded states in (a segment's starting point)
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void load_hidden_kernel(const T* __restrict__ in, float* __restrict__ resid, int d) {
+    const int64_t n = blockIdx.x;
+    const T* src = in + n * (int64_t)d;
+    float* dp = resid + n * (int64_t)d;
+    for (int i = threadIdx.x; i < d; i += ROW_THREADS) dp[i] = to_f32(src[i]);
+}
+
+void launch_load_hidden(const void* in, int dtype, float* resid, int64_t rows, int d, hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == VL_BF16)
+        load_hidden_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const bf16*)in, resid, d);
+    else
+        load_hidden_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const float*)in, resid, d);
+}
+
 __global__ void scatter_i32_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ out,
                                    const int32_t* __restrict__ dst, int64_t rows) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -109,6 +109,28 @@ def run_verify(ctx: P.Context, wl: synth.Workload, tokens: np.ndarray, committed
     return d_flags.cpu().numpy()[:n], stats, sm.as_dict()
 
 
+def run_verify_segment(ctx: P.Context, wl: synth.Workload, tokens, start_layer: int, end_layer: int, upstream_stored,
+                       commit_layers, committed_stored: np.ndarray, committed_argmax, tol=None):
+    """Calls vl_verify_segment; upstream/committed arrays are in the workload's stored dtype.  Same returns as run_verify."""
+    n = int(sum(wl.lengths))
+    c = len(commit_layers)
+    d_tok = to_dev(np.asarray(tokens).astype(np.int32)) if tokens is not None else None
+    d_up = to_dev(upstream_stored) if upstream_stored is not None else None
+    d_com = to_dev(committed_stored)
+    d_cam = to_dev(np.asarray(committed_argmax, dtype=np.int32)) if committed_argmax is not None else None
+    d_flags = torch.zeros(max(n, 1), dtype=torch.uint8, device=DEV)
+    d_stats = torch.zeros(max(c * n, 1) * 4, dtype=torch.float32, device=DEV)
+    tol = tol or P.Tol(wl.tol_rel_l2, wl.tol_max_abs, wl.tol_logit_margin)
+    code = hidden_dtype_code(wl.hidden_dtype)
+    sm = ctx.vl_verify_segment(start_layer, end_layer, d_up.data_ptr() if d_up is not None else 0, code,
+                               d_tok.data_ptr() if d_tok is not None else 0, wl.lengths, list(commit_layers), d_com.data_ptr(), code,
+                               d_cam.data_ptr() if d_cam is not None else 0, tol, d_flags.data_ptr(), d_stats.data_ptr())
+    st = d_stats.cpu().numpy()[: c * n * 4].reshape(c, n, 4)
+    stats = [{"rel_l2": st[i, :, 0], "max_abs": st[i, :, 1], "mean_abs": st[i, :, 2], "mean_signed": st[i, :, 3]}
+             for i in range(c)]
+    return d_flags.cpu().numpy()[:n], stats, sm.as_dict()
+
+
 def run_commit(ctx: P.Context, wl: synth.Workload, tokens: np.ndarray, mode: str, prompt_lens=None,
                want_argmax: bool = True):
     """vl_prefill_commit (mode 'prefill') or vl_decode_commit (mode 'decode').

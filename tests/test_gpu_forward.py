@@ -6,6 +6,7 @@ Small shapes that still span several GEMM / attention tiles and ragged tails.  T
                layer, logits max-abs <= 5e-2, argmax equal wherever the oracle's top-2 gap is >= 0.1
 Flags must be bit-exact: honest noise is far below the acceptance tolerance, tampering far above it.
 """
+import dataclasses
 import math
 import sys
 
@@ -285,6 +286,97 @@ def test_edge_cases_and_error_paths(small_bf16):
         assert e.value.code == -1
         with pytest.raises(P.VerilLMError) as e:
             ctx2.vl_verify_prefill(d_tok.data_ptr(), [10], [1], d_tok.data_ptr(), P.VL_BF16, 0, tol, d_flags.data_ptr())
+        assert e.value.code == -2
+    finally:
+        ctx2.close()
+
+
+# ====================================================================================== segment-local verification
+def check_segment_against_oracle(ctx, om, wl, x, hid, z, lo, hi, layers, tol_hidden, with_tokens_arg=True):
+    """One verifier of blocks lo+1 .. hi: upstream = the oracle's recorded states of layer lo (stored dtype), tampered
+    commitments inside the segment; the GPU and the oracle's segment verifier must agree flag for flag."""
+    n = wl.n_tokens
+    wls = dataclasses.replace(wl, commit_layers=tuple(layers), check_argmax=(hi == wl.model.n_layers))
+    pos = synth.tamper_positions(wls)
+    committed = np.stack([hid[l] for l in layers]).astype(np.float32)
+    com_st = H.stored(synth.tamper_hidden(wls, committed, pos), wl.hidden_dtype)
+    up_st = H.stored(hid[lo].astype(np.float32), wl.hidden_dtype) if lo else None
+    cam = None
+    if hi == wl.model.n_layers:
+        cam, _ = synth.tamper_argmax(wls, O.argmax_lowest(z).astype(np.int32), pos, wrong_tokens=np.argmin(z, axis=1))
+    flags, stats, sm = H.run_verify_segment(ctx, wls, x if (lo == 0 or with_tokens_arg) else None, lo, hi, up_st, layers, com_st, cam)
+    ref = O.verify(om, x, wl.lengths, layers, com_st, cam, wls.tol_rel_l2, wls.tol_max_abs, wls.tol_logit_margin,
+                   start_layer=lo, upstream_hidden=up_st, end_layer=hi)
+    expect = np.ones(n, np.uint8)
+    expect[pos] = 0
+    np.testing.assert_array_equal(ref["flags"], expect)
+    np.testing.assert_array_equal(flags, ref["flags"])
+    for c in range(len(layers)):
+        assert np.abs(stats[c]["rel_l2"] - ref["stats"][c]["rel_l2"]).max() <= tol_hidden * 1.5
+    assert sm["n_rejected"] == ref["summary"]["n_rejected"] == len(pos)
+    return stats
+
+
+def test_tiny_f32_segment_verifiers_match_oracle(tiny):
+    ctx, om, wl, x = tiny
+    hid, z = O.prefill(om, x, wl.lengths, [1, 2])
+    say("tiny f32 segment (0,1] from tokens")
+    check_segment_against_oracle(ctx, om, wl, x, hid, z, 0, 1, [1], 1e-5)
+    say("tiny f32 segment (1,2] from recorded states, with the token check, tokens pointer NULL")
+    check_segment_against_oracle(ctx, om, wl, x, hid, z, 1, 2, [2], 1e-5, with_tokens_arg=False)
+
+
+def test_small_bf16_segment_verifiers_match_oracle(small_bf16):
+    ctx, om, wl, x = small_bf16
+    hid, z = O.prefill(om, x, wl.lengths, [1, 2, 3])
+    say("small bf16 segment (1,3] committing layers 2 and 3, token check at the end")
+    st = check_segment_against_oracle(ctx, om, wl, x, hid, z, 1, 3, [2, 3], 2e-2)
+    say("small bf16 segment (0,2] without a token check")
+    check_segment_against_oracle(ctx, om, wl, x, hid, z, 0, 2, [1, 2], 2e-2)
+    say("small bf16 segment (2,3]: one block from recorded states is closer to the oracle than three blocks from tokens")
+    st1 = check_segment_against_oracle(ctx, om, wl, x, hid, z, 2, 3, [3], 2e-2)
+    val, _, _ = H.run_commit(ctx, wl, x, "prefill")
+    honest = np.ones(wl.n_tokens, bool)
+    honest[synth.tamper_positions(wl)] = False
+    whole = H.rel_l2_rows(val[1], hid[3])
+    assert np.median(st1[0]["rel_l2"][honest]) < np.median(whole[honest])
+
+
+def test_segment_argument_errors_and_partial_weights(small_bf16):
+    ctx, om, wl, x = small_bf16
+    m = wl.model
+    n = 20
+    d_tok = H.to_dev(np.zeros(n, np.int32))
+    d_hid = torch.zeros((n, m.d_model), dtype=torch.int16, device=H.DEV)
+    d_flags = torch.zeros(n, dtype=torch.uint8, device=H.DEV)
+    tol = P.Tol(0.1, math.inf, 0.25)
+
+    def call(c, lo, hi, up, layers, cam=0, tok=None):
+        return c.vl_verify_segment(lo, hi, up, P.VL_BF16, d_tok.data_ptr() if tok is None else tok, [n], layers, d_hid.data_ptr(),
+                                   P.VL_BF16, cam, tol, d_flags.data_ptr())
+
+    say("segment errors: empty or reversed range, layers outside, token check before the last layer, NULL upstream / tokens")
+    for lo, hi, up, layers, cam, tok in [(2, 2, d_hid.data_ptr(), [2], 0, None), (2, 1, d_hid.data_ptr(), [2], 0, None),
+                                         (0, 4, 0, [1], 0, None), (-1, 2, 0, [1], 0, None), (1, 3, d_hid.data_ptr(), [1], 0, None),
+                                         (0, 2, 0, [3], 0, None), (0, 2, 0, [1], d_tok.data_ptr(), None),
+                                         (1, 3, 0, [2], 0, None), (0, 2, 0, [1], 0, 0)]:
+        with pytest.raises(P.VerilLMError) as e:
+            call(ctx, lo, hi, up, layers, cam, tok)
+        assert e.value.code == -1, (lo, hi, layers)
+    say("segment with only its own blocks loaded: runs; the whole-model call and other segments report missing weights")
+    ctx2 = P.Context(H.c_cfg(m, 64, 2, 64), 0, 0)
+    try:
+        for k in synth.PER_LAYER_KINDS:
+            w = np.ascontiguousarray(synth.weight(m, k, 1))
+            ctx2.vl_load_weights(k, 1, w.ctypes.data, w.nbytes)
+        sm = call(ctx2, 1, 2, d_hid.data_ptr(), [2])
+        assert sm.as_dict()["n_tokens"] == n
+        for args in [(0, 2, 0, [2]), (1, 3, d_hid.data_ptr(), [2]), (1, 3, d_hid.data_ptr(), [3], d_tok.data_ptr())]:
+            with pytest.raises(P.VerilLMError) as e:
+                call(ctx2, *args)
+            assert e.value.code == -2, args
+        with pytest.raises(P.VerilLMError) as e:
+            ctx2.vl_verify_prefill(d_tok.data_ptr(), [n], [1], d_hid.data_ptr(), P.VL_BF16, 0, tol, d_flags.data_ptr())
         assert e.value.code == -2
     finally:
         ctx2.close()

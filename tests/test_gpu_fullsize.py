@@ -177,6 +177,38 @@ def test_workload1_decode_commitments_verify_clean(ctx_8b):
     np.testing.assert_array_equal(flags, expect)
     assert sm["n_rejected"] == len(pos)
 
+    say("workload 1: the four segment verifiers, each from the honest record of its upstream boundary")
+    st_t = H.stored(com_t, "bf16")
+    for ci, hi in enumerate(wl.commit_layers):
+        lo = wl.commit_layers[ci - 1] if ci else 0
+        last = hi == wl.model.n_layers
+        f, stt, sm = H.run_verify_segment(ctx_8b, wl, x if lo == 0 else None, lo, hi, st_d[ci - 1] if ci else None, [hi],
+                                          st_t[ci][None], cam_t if last else None)
+        np.testing.assert_array_equal(f, expect)
+        honest = expect.astype(bool)
+        print(f"  segment ({lo},{hi}]: honest rel-L2 max {stt[0]['rel_l2'][honest].max():.2e}, {sm['ms_forward']:.1f} ms", flush=True)
+        assert stt[0]["rel_l2"][honest].max() <= wl.tol_rel_l2 / 2
+
+    say("workload 1: segment (8,16] against the oracle's segment verifier on the first 64 rows of sequence 2")
+    cu = synth.cu_seqlens(wl.lengths)
+    r0 = int(cu[2])
+    rows = np.arange(r0, r0 + 64)
+    f, stt, _ = H.run_verify_segment(ctx_8b, wl, None, 8, 16, st_d[0], [16], st_t[1][None], None)
+    ref_stats = {}
+    for mode in (None, "bf16"):
+        om = H.oracle_model(wl.model, progress="", operand_dtype=mode)
+        ref = O.verify(om, x[rows], [64], [16], st_t[1][rows][None], None, 0.1, math.inf, 0.25, start_layer=8,
+                       upstream_hidden=st_d[0][rows], end_layer=16)
+        ref_stats[mode] = ref
+    np.testing.assert_array_equal(f[rows], ref_stats[None]["flags"])
+    np.testing.assert_array_equal(f[rows], ref_stats["bf16"]["flags"])
+    # the statistic is |GPU state - record| / |GPU state|; it moves by at most the GPU-vs-oracle distance of the states,
+    # which for 8 blocks from a common start is bounded as in sampled_check
+    d_exact = np.abs(stt[0]["rel_l2"][rows] - ref_stats[None]["stats"][0]["rel_l2"]).max()
+    d_fmt = np.abs(stt[0]["rel_l2"][rows] - ref_stats["bf16"]["stats"][0]["rel_l2"]).max()
+    print(f"  rel-L2 statistic vs oracle: exact-arithmetic model {d_exact:.2e}, bf16-operand model {d_fmt:.2e}", flush=True)
+    assert d_exact <= 1.25e-2 * math.sqrt(8) and d_fmt <= 0.75e-2 * math.sqrt(8)
+
 
 def test_workload2_8b_varlen64(ctx_8b):
     wl = synth.workload(2)

@@ -131,6 +131,43 @@ def test_segment_local_prefill_composes_to_full_prefill():
     assert z_first is None
 
 
+def test_segment_verifiers_accept_honest_states_and_localise_a_fault():
+    # Section 5.6: every segment is judged on its own from the recorded upstream states.  What must hold follows from
+    # causality and from the independence of sequences, not from the code: a fault planted in the record of layer 2 at
+    # position p of sequence 1 is seen by the verifier of (1,2] at p only; the verifier of (2,3] starts from the
+    # faulty record, so its recomputation can differ at p and at later positions of the same sequence, nowhere else;
+    # the verifier of (0,1] sees nothing.
+    m = make_model(TINY)
+    lengths = [6, 9, 4]
+    x = toks(sum(lengths), TINY.vocab, 8)
+    h, z = O.prefill(m, x, lengths, [1, 2, 3])
+    com = {l: h[l].astype(np.float32) for l in (1, 2, 3)}
+    cam = O.argmax_lowest(z).astype(np.int32)
+    tol = dict(tol_rel_l2=1e-4, tol_max_abs=np.inf, tol_logit_margin=1e-3)
+    whole = O.verify(m, x, lengths, [1, 2, 3], np.stack([com[1], com[2], com[3]]), cam, **tol)
+    assert whole["flags"].all()
+    for lo, hi in ((0, 1), (1, 2), (2, 3)):
+        seg = O.verify(m, x, lengths, [hi], com[hi][None], cam if hi == 3 else None, start_layer=lo,
+                       upstream_hidden=com[lo] if lo else None, end_layer=hi, **tol)
+        assert seg["flags"].all() and seg["stats"][0]["rel_l2"].max() < 1e-6
+    p = 6 + 3                                             # position 3 of sequence 1 (rows 6 .. 14)
+    bad = com[2].copy()
+    bad[p] += 0.05 * np.abs(com[2][p]).max()
+    s01 = O.verify(m, x, lengths, [1], com[1][None], None, end_layer=1, **tol)
+    s12 = O.verify(m, x, lengths, [2], bad[None], None, start_layer=1, upstream_hidden=com[1], end_layer=2, **tol)
+    s23 = O.verify(m, x, lengths, [3], com[3][None], cam, start_layer=2, upstream_hidden=bad, end_layer=3, **tol)
+    assert s01["flags"].all()
+    expect = np.ones(sum(lengths), np.uint8)
+    expect[p] = 0
+    np.testing.assert_array_equal(s12["flags"], expect)
+    assert s23["flags"][p] == 0
+    untouched = np.r_[0:p, 15:19]                         # earlier rows of the sequence and the other sequences
+    assert s23["flags"][untouched].all() and s23["stats"][0]["rel_l2"][untouched].max() < 1e-6
+    assert (s23["stats"][0]["rel_l2"][p + 1:15] > 1e-6).all()    # later rows do feel the fault through attention
+    w = O.verify(m, x, lengths, [1, 2, 3], np.stack([com[1], bad, com[3]]), cam, **tol)
+    np.testing.assert_array_equal(w["flags"], expect)     # the whole-model verifier recomputes layer 3 from its own state
+
+
 def test_gqa_equals_mha_with_replicated_kv_heads():
     gqa = synth.ModelCfg("g", 1, 32, 4, 2, 8, 48, 64, 1e-5, 10000.0, "f32", 0.3, seed=9)
     mha = synth.ModelCfg("m", 1, 32, 4, 4, 8, 48, 64, 1e-5, 10000.0, "f32", 0.3, seed=9)
