@@ -27,6 +27,10 @@ causal attention scaled by 1/sqrt(head_dim), SwiGLU feed-forward, no biases, unt
 RMSNorm).  The "hidden state after layer l" is the residual stream leaving block l, before any
 following norm, for every l including the last.
 
+* Section 7 "Bit-aware statistical comparison" (P_e, P_m, P_w, mean discrepancy and their calibrated
+  thresholds) and the offline test battery of Appendix A.1 (P_exp, Q_small, Z_large, MAE)
+                                                                                -> `bit_compare`, `bit_rule`.
+
 Readings that go beyond the paper (per-token relative L2 and max-abs instead of one verdict per
 segment; a logit margin for near-tied argmax) are documented where they are implemented.
 
@@ -317,6 +321,87 @@ def compare_hidden(h_hat: np.ndarray, h_star: np.ndarray, tol_rel_l2: float, tol
         mean_signed = np.mean(delta, axis=-1)
         ok = (rel <= tol_rel_l2) & (mx <= tol_max_abs)
     return {"rel_l2": rel, "max_abs": mx, "mean_abs": mean_abs, "mean_signed": mean_signed, "ok": ok}
+
+
+
+# ----------------------------------------------------------------------------------------------
+# Bit-aware comparison (Section 7, "Bit-aware statistical comparison") and the battery of offline tests
+# of the quantization-attack analysis (Appendix A.1: P_exp, Q_small, Z_large, MAE)
+# ----------------------------------------------------------------------------------------------
+
+def float32_fields(x: np.ndarray):
+    """Sign, exponent and mantissa fields of float32 values: bit 31, bits 30..23, bits 22..0."""
+    bits = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    return (bits >> np.uint32(31)).astype(np.int64), ((bits >> np.uint32(23)) & np.uint32(0xFF)).astype(np.int64), \
+        (bits & np.uint32(0x7FFFFF)).astype(np.int64)
+
+
+def bit_compare(h_hat: np.ndarray, h_star: np.ndarray, e_w: float, e_m: int, step_log2: int,
+                q_small: float, tau_large: float) -> dict:
+    """Per-token counts behind P_e, P_m, P_w, Q_small, Z_large of the recomputed state against the record.
+
+    Both operands are taken in canonical float32 (the record upcast exactly from its stored dtype; the
+    recomputation rounded to float32 if it is wider) and every element is split into its fields.
+    Delta = h_hat - h_star is the float32 difference.  Per row of d elements:
+
+      n_exact          both bit patterns identical
+      n_exp_mismatch   exponent fields differ                                  -> P_e = n_exp_mismatch / d
+      n_mismatch_close among those, |Delta| <= e_w                             -> P_m = n_mismatch_close / n_exp_mismatch
+      n_match_small    among equal exponent fields, mantissa fields at most e_m steps apart, one step being
+                       2**step_log2 units of the float32 mantissa               -> P_w = n_match_small / (d - n_exp_mismatch)
+      n_small          |Delta| <= q_small                                      -> Q_small = n_small / d
+      n_large          |Delta| >  tau_large                                    -> Z_large = n_large / d
+
+    Readings.  The text defines P_m as the share of "large mantissa deviations among exponent mismatches" and
+    accepts when it is HIGH, and gives a value tolerance e_w that no other quantity uses: read as "the exponent
+    differs only because the value sits next to a power of two", i.e. the two values are within e_w of each
+    other although their mantissa fields are far apart.  The mantissa tolerance e_m counts steps of the
+    record's storage format (step_log2 = 0 for float32 records, 16 for bf16 ones, whose mantissa has 7 bits).
+    The sign bit enters none of the counts; a sign error shows in Delta.  A NaN makes every <=, > test false.
+    """
+    a = np.asarray(h_hat)
+    a = a.astype(np.float32) if a.dtype != np.uint16 else upcast(a).astype(np.float32)
+    b = upcast(h_star).astype(np.float32)
+    _, ea, ma = float32_fields(a)
+    _, eb, mb = float32_fields(b)
+    with np.errstate(invalid="ignore", over="ignore"):
+        delta = (a - b).astype(np.float32)
+        ad = np.abs(delta)
+        mism = ea != eb
+        close = ad <= np.float32(e_w)
+        small_m = np.abs(ma - mb) <= (int(e_m) << int(step_log2))
+        return {
+            "n_exact": np.sum(a.view(np.uint32) == b.view(np.uint32), axis=-1),
+            "n_exp_mismatch": np.sum(mism, axis=-1),
+            "n_mismatch_close": np.sum(mism & close, axis=-1),
+            "n_match_small": np.sum(~mism & small_m, axis=-1),
+            "n_small": np.sum(ad <= np.float32(q_small), axis=-1),
+            "n_large": np.sum(ad > np.float32(tau_large), axis=-1),
+            "d": a.shape[-1],
+        }
+
+
+def bit_rule(counts: dict, mean_signed: np.ndarray, pe_max: float, pm_min: float, pw_min: float, eps_max: float,
+             q_small_min: float = 0.0, z_large_max: float = 1.0) -> np.ndarray:
+    """The acceptance rule on top of `bit_compare`: P_e < pe_max, P_m > pm_min, P_w > pw_min, |mean Delta| <= eps_max
+    (the paper's calibrated off-chain values: 0.05, 0.75, 0.80, 0.01), and the two battery bounds
+    Q_small >= q_small_min, Z_large <= z_large_max (calibrated per deployment; the defaults switch them off).
+
+    A ratio over an empty set passes.  Every ratio test is taken as `count (<|>) bound * size` in float32,
+    which is how an implementation without a division decides it; mean_signed [N] comes from `compare_hidden`.
+    """
+    f = np.float32
+    d = f(counts["d"])
+    mis = counts["n_exp_mismatch"].astype(np.float32)
+    match = d - mis
+    with np.errstate(invalid="ignore"):
+        ok = mis < f(pe_max) * d
+        ok &= (mis == 0) | (counts["n_mismatch_close"].astype(np.float32) > f(pm_min) * mis)
+        ok &= (match == 0) | (counts["n_match_small"].astype(np.float32) > f(pw_min) * match)
+        ok &= np.abs(np.asarray(mean_signed, dtype=np.float64)) <= float(f(eps_max))
+        ok &= counts["n_small"].astype(np.float32) >= f(q_small_min) * d
+        ok &= counts["n_large"].astype(np.float32) <= f(z_large_max) * d
+    return ok
 
 
 def token_check(logits: np.ndarray, committed_argmax: np.ndarray, margin: float):
