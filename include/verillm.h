@@ -110,6 +110,36 @@ typedef struct {
     float   ms_forward, ms_compare;/* device time of the call: everything, and the compare/argmax part    */
 } vl_summary;
 
+/* Section 7 "Bit-aware statistical comparison" and the offline test battery of Appendix A.1 (P_exp, Q_small,
+   Z_large, MAE).  Both states are taken as canonical float32 (a bf16 record is upcast exactly) and split into the
+   exponent field (bits 30..23) and the mantissa field (bits 22..0); Delta is the float32 difference
+   recomputed - recorded; the sign bit enters no count.  Per token, over the d_model elements of a state:
+     P_e = n_exp_mismatch / d
+     P_m = n_mismatch_close / n_exp_mismatch      close: |Delta| <= e_w although the exponent fields differ
+     P_w = n_match_small / (d - n_exp_mismatch)   small: mantissa fields at most e_m steps apart, one step being
+                                                  2^step_log2 units of the float32 mantissa (0 for float32 records,
+                                                  16 for bf16 records, whose mantissa has 7 bits)
+     Q_small = n_small / d (|Delta| <= q_small),  Z_large = n_large / d (|Delta| > tau_large)
+   The rule accepts a token iff P_e < pe_max, P_m > pm_min, P_w > pw_min, |mean Delta| <= eps_max,
+   Q_small >= q_small_min and Z_large <= z_large_max; a ratio over an empty set passes; each ratio test is decided
+   as count vs bound * size in float32.  The paper's calibrated off-chain values are pe_max 0.05, pm_min 0.75,
+   pw_min 0.80, eps_max 0.01 with e_w = 1e-2, e_m = 7, q_small = 1e-5; q_small_min = 0 and z_large_max = 1 switch
+   the two battery bounds off. */
+typedef struct {
+    float   e_w;
+    int32_t e_m;                   /* >= 0 */
+    int32_t step_log2;             /* 0 .. 23 */
+    float   q_small, tau_large;
+    float   pe_max, pm_min, pw_min, eps_max, q_small_min, z_large_max;
+} vl_bit_rule;
+
+typedef struct {
+    int32_t  n_exact;              /* identical bit patterns */
+    int32_t  n_exp_mismatch, n_mismatch_close, n_match_small, n_small, n_large;
+    float    mean_signed;          /* mean Delta, as in vl_tok_stats */
+    uint32_t ok;                   /* 1 iff the rule accepts the token at this layer */
+} vl_bit_stats;
+
 /* ---- life cycle ------------------------------------------------------------------------------- */
 
 /* Validate `cfg` and report the device memory vl_create would allocate for it.  Host only; touches no GPU.
@@ -202,6 +232,18 @@ int vl_decode_commit(vl_ctx* ctx,
                      const int32_t* commit_layers, int32_t C,
                      void* out_hidden, int32_t hidden_dtype, int32_t* out_argmax);
 
+/* Switch the bit-aware rule on (rule != NULL; the struct is copied) or off (NULL, the default) for later
+   vl_verify_prefill / vl_verify_segment calls on this context.  While on, every committed layer is additionally
+   judged by the rule in the same pass over the data, a token's hidden check passes only if the tolerance test AND
+   the rule pass at every committed layer, and the per-token counts are kept for vl_get_bit_stats.
+   VL_E_ARG for e_m < 0, step_log2 outside [0, 23] or a NaN field. */
+int vl_set_bit_rule(vl_ctx* ctx, const vl_bit_rule* rule);
+
+/* Counts of commit-layer index c (0-based position in that call's commit_layers) for rows [tok_begin, tok_end) of
+   the most recent verify call made while a rule was set: out [device] vl_bit_stats [tok_end - tok_begin].
+   VL_E_ARG if that call had no rule, or c / the range is outside it. */
+int vl_get_bit_stats(vl_ctx* ctx, int32_t c, int64_t tok_begin, int64_t tok_end, vl_bit_stats* out);
+
 /* ---- inspection of the most recent vl_verify_prefill / vl_prefill_commit (parity checks) ------- */
 
 /* Copy logits rows [tok_begin, tok_end) of the most recent call that ran the LM head: out [device] float32
@@ -251,6 +293,12 @@ int vl_op_compare(vl_ctx* ctx, const float* h_hat, const void* committed, int32_
    or NULL; outputs [device], any may be NULL. */
 int vl_op_argmax(vl_ctx* ctx, const float* logits, int64_t N, const int32_t* committed_argmax, float margin,
                  int32_t* out_argmax, float* out_gap, uint8_t* out_ok);
+
+/* vl_op_compare plus the bit-aware rule on the same rows: h_hat [device] float32 [N][d_model], committed [device]
+   [N][d_model] in hidden_dtype; stats [device] out vl_tok_stats [N] or NULL, bits [device] out vl_bit_stats [N] or
+   NULL, ok [device] out uint8 [N] (tolerance test AND rule) or NULL. */
+int vl_op_compare_bits(vl_ctx* ctx, const float* h_hat, const void* committed, int32_t hidden_dtype, int64_t N,
+                       const vl_tol* tol, const vl_bit_rule* rule, vl_tok_stats* stats, vl_bit_stats* bits, uint8_t* ok);
 
 #ifdef __cplusplus
 }

@@ -459,7 +459,8 @@ def summary(stats: Sequence[dict], token_ok: Optional[np.ndarray], flag: np.ndar
 def verify(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: Sequence[int],
            committed_hidden: np.ndarray, committed_argmax: Optional[np.ndarray],
            tol_rel_l2: float, tol_max_abs: float, tol_logit_margin: float,
-           start_layer: int = 0, upstream_hidden: Optional[np.ndarray] = None, end_layer: Optional[int] = None):
+           start_layer: int = 0, upstream_hidden: Optional[np.ndarray] = None, end_layer: Optional[int] = None,
+           bit_params: Optional[dict] = None, bit_thresholds: Optional[dict] = None):
     """The whole hot path: prefill, compare at every committed layer, token check, flags, summary.
 
     committed_hidden [C, N, d] in stored dtype.  Returns dict with hidden, logits, stats (list over C),
@@ -469,6 +470,10 @@ def verify(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: 
     it takes the recorded states entering block start_layer+1 as given (upstream_hidden [N, d], stored
     dtype), recomputes blocks start_layer+1 .. end_layer only and judges the commitments inside that range.
     The token check belongs to the segment that ends at the last layer.
+
+    With bit_params (keyword arguments of `bit_compare`) and bit_thresholds (those of `bit_rule`) every committed
+    layer is also judged by the bit-aware rule of Section 7: a token passes a layer only if both the tolerance
+    test and the rule pass; the counts are returned in stats[c]["bits"], the rule's verdict in stats[c]["bit_ok"].
     """
     end_layer = m.L if end_layer is None else end_layer
     assert 0 <= start_layer < end_layer <= m.L
@@ -480,6 +485,12 @@ def verify(m: Model, tokens: np.ndarray, lengths: Sequence[int], commit_layers: 
                              end_layer=end_layer)
     stats = [compare_hidden(hidden[l], committed_hidden[c], tol_rel_l2, tol_max_abs)
              for c, l in enumerate(commit_layers)]
+    if bit_params is not None:
+        for c, l in enumerate(commit_layers):
+            counts = bit_compare(hidden[l], committed_hidden[c], **bit_params)
+            stats[c]["bits"] = counts
+            stats[c]["bit_ok"] = bit_rule(counts, stats[c]["mean_signed"], **bit_thresholds)
+            stats[c]["ok"] = stats[c]["ok"] & stats[c]["bit_ok"]
     if committed_argmax is not None:
         a, gap, tok_ok = token_check(logits, committed_argmax, tol_logit_margin)
     else:

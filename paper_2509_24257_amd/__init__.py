@@ -4,6 +4,6 @@
 as include/verillm.h; every step of the path runs inside that library's HIP kernels.
 """
 from .binding import (  # noqa: F401
-    VL_BF16, VL_F32, VerilLMError, Context, ModelCfg, Summary, Tol, TokStats, lib, lib_path, load_library,
+    VL_BF16, VL_F32, VerilLMError, Context, ModelCfg, Summary, Tol, TokStats, BitRule, BitStats, lib, lib_path, load_library,
     vl_plan_memory,
 )

@@ -15,9 +15,9 @@ VL_OK, VL_E_ARG, VL_E_WEIGHTS, VL_E_CAPACITY, VL_E_HIP, VL_E_NOMEM = 0, -1, -2, 
 _STATUS = {0: "VL_OK", -1: "VL_E_ARG", -2: "VL_E_WEIGHTS", -3: "VL_E_CAPACITY", -4: "VL_E_HIP", -5: "VL_E_NOMEM"}
 
 EXPORTS = ["vl_plan_memory", "vl_create", "vl_load_weights", "vl_destroy", "vl_last_error", "vl_verify_prefill",
-           "vl_verify_segment", "vl_prefill_commit", "vl_decode_commit", "vl_get_logits", "vl_get_argmax", "vl_profile_enable",
-           "vl_profile_read", "vl_op_gemm_bf16",
-           "vl_op_attention_bf16", "vl_op_compare", "vl_op_argmax"]
+           "vl_verify_segment", "vl_prefill_commit", "vl_decode_commit", "vl_get_logits", "vl_get_argmax",
+           "vl_set_bit_rule", "vl_get_bit_stats", "vl_profile_enable", "vl_profile_read", "vl_op_gemm_bf16",
+           "vl_op_attention_bf16", "vl_op_compare", "vl_op_compare_bits", "vl_op_argmax"]
 
 
 STAGES = ["embed", "norm", "qkv_gemm", "rope", "attention", "o_gemm", "gateup_gemm", "down_gemm", "compare", "lm_gemm",
@@ -37,6 +37,18 @@ class Tol(C.Structure):
 
 class TokStats(C.Structure):
     _fields_ = [("rel_l2", C.c_float), ("max_abs", C.c_float), ("mean_abs", C.c_float), ("mean_signed", C.c_float)]
+
+
+class BitRule(C.Structure):
+    _fields_ = [("e_w", C.c_float), ("e_m", C.c_int32), ("step_log2", C.c_int32), ("q_small", C.c_float), ("tau_large", C.c_float),
+                ("pe_max", C.c_float), ("pm_min", C.c_float), ("pw_min", C.c_float), ("eps_max", C.c_float),
+                ("q_small_min", C.c_float), ("z_large_max", C.c_float)]
+
+
+class BitStats(C.Structure):
+    _fields_ = [("n_exact", C.c_int32), ("n_exp_mismatch", C.c_int32), ("n_mismatch_close", C.c_int32),
+                ("n_match_small", C.c_int32), ("n_small", C.c_int32), ("n_large", C.c_int32), ("mean_signed", C.c_float),
+                ("ok", C.c_uint32)]
 
 
 class Summary(C.Structure):
@@ -87,6 +99,9 @@ def load_library():
     lib.vl_decode_commit.argtypes = [vp, vp, i32p, i32p, C.c_int32, i32p, C.c_int32, vp, C.c_int32, vp]
     lib.vl_get_logits.argtypes = [vp, C.c_int64, C.c_int64, vp]
     lib.vl_get_argmax.argtypes = [vp, C.c_int64, C.c_int64, vp, vp]
+    lib.vl_set_bit_rule.argtypes = [vp, C.POINTER(BitRule)]
+    lib.vl_get_bit_stats.argtypes = [vp, C.c_int32, C.c_int64, C.c_int64, vp]
+    lib.vl_op_compare_bits.argtypes = [vp, vp, vp, C.c_int32, C.c_int64, C.POINTER(Tol), C.POINTER(BitRule), vp, vp, vp]
     lib.vl_profile_enable.argtypes = [vp, C.c_int]
     lib.vl_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.vl_op_gemm_bf16.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
@@ -192,6 +207,18 @@ class Context:
     def vl_get_argmax(self, tok_begin: int, tok_end: int, out_argmax: int = 0, out_gap: int = 0):
         self._check(lib().vl_get_argmax(self._h, int(tok_begin), int(tok_end), C.c_void_p(out_argmax or None),
                                         C.c_void_p(out_gap or None)))
+
+    def vl_set_bit_rule(self, rule: Optional[BitRule]):
+        self._check(lib().vl_set_bit_rule(self._h, C.byref(rule) if rule is not None else None))
+
+    def vl_get_bit_stats(self, c: int, tok_begin: int, tok_end: int, out: int):
+        self._check(lib().vl_get_bit_stats(self._h, int(c), int(tok_begin), int(tok_end), C.c_void_p(out or None)))
+
+    def vl_op_compare_bits(self, h_hat: int, committed: int, hidden_dtype: int, n: int, tol: Tol, rule: BitRule, stats: int,
+                           bits: int, ok: int):
+        self._check(lib().vl_op_compare_bits(self._h, C.c_void_p(h_hat or None), C.c_void_p(committed or None), int(hidden_dtype),
+                                             int(n), C.byref(tol), C.byref(rule), C.c_void_p(stats or None),
+                                             C.c_void_p(bits or None), C.c_void_p(ok or None)))
 
     def vl_profile_enable(self, mode: int):
         self._check(lib().vl_profile_enable(self._h, int(mode)))

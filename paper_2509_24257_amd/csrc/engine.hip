@@ -97,6 +97,7 @@ Plan make_plan(const vl_model_cfg& c) {
     w += align_up(p.T * (c.head_dim / 2) * 8, ALIGN);    // rotary cos/sin table
     w += align_up(p.stage_ints * 4, ALIGN);              // per-call index arrays
     w += align_up((int64_t)p.L * p.N * (int64_t)sizeof(vl_tok_stats), ALIGN);
+    w += align_up((int64_t)p.L * p.N * (int64_t)sizeof(vl_bit_stats), ALIGN);
     w += 3 * align_up(p.N, ALIGN) + align_up(p.N * 4, ALIGN) * 2 + ALIGN;   // ok bytes, argmax, gap, summary
     p.workspace_total = w;
     return p;
@@ -134,6 +135,10 @@ struct vl_ctx {
     int32_t* d_idx = nullptr;           // device copy of the per-call index arrays
     int32_t* h_idx = nullptr;           // pinned host staging for them
     vl_tok_stats* stats = nullptr;
+    vl_bit_stats* bit_stats = nullptr;  // [L][N], written only while a bit rule is set
+    bool has_rule = false;
+    vl_bit_rule rule{};
+    int last_bits_c = 0;                // committed layers of the most recent verify call that ran the rule
     uint8_t* hid_ok = nullptr;
     uint8_t* tok_ok = nullptr;
     uint8_t* scratch_ok = nullptr;
@@ -414,6 +419,7 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
     HIP_TRY(c, hipSetDevice(c->device));
     c->last_n = 0;
     c->last_has_logits = false;
+    c->last_bits_c = 0;
     if (summary) memset(summary, 0, sizeof(*summary));
     if (n == 0) return VL_OK;
     if (verify && C > 0 && !committed_hidden) return c->fail(VL_E_ARG, "committed_hidden is NULL");
@@ -454,7 +460,8 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
                 {
                     StageSpan sp(c, VL_STAGE_COMPARE);
                     launch_compare(c->resid, (const char*)committed_hidden + off, hidden_dtype, n, m.d_model, tol->rel_l2, tol->max_abs,
-                                   c->stats + (int64_t)ci * n, c->hid_ok, nullptr, s);
+                                   c->stats + (int64_t)ci * n, c->hid_ok, nullptr, s, c->has_rule ? &c->rule : nullptr,
+                                   c->bit_stats + (int64_t)ci * n);
                 }
                 HIP_TRY(c, hipEventRecord(b, s));
                 cmp_spans.push_back({a, b});
@@ -493,6 +500,7 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
     collect_profile(c);
     c->last_n = n;
     c->last_has_logits = run_head;
+    c->last_bits_c = (verify && c->has_rule) ? C : 0;
     if (summary) {
         float ms = 0.f;
         HIP_TRY(c, hipEventElapsedTime(&ms, e_start, e_stop));
@@ -591,6 +599,7 @@ int vl_create(const vl_model_cfg* cfg, int device, void* hip_stream, vl_ctx** ou
     if ((rc = dev_alloc(c, &c->rope_cs, p.T * (cfg->head_dim / 2) * 8, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->d_idx, p.stage_ints * 4, true))) return bail(rc);
     if ((rc = dev_alloc(c, &c->stats, p.L * p.N * (int64_t)sizeof(vl_tok_stats), false))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->bit_stats, p.L * p.N * (int64_t)sizeof(vl_bit_stats), false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->hid_ok, p.N, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->tok_ok, p.N, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->scratch_ok, p.N, false))) return bail(rc);
@@ -691,6 +700,36 @@ int vl_verify_segment(vl_ctx* c, int32_t start_layer, int32_t end_layer, const v
     const Segment seg{start_layer, end_layer, upstream_hidden, upstream_dtype};
     return run_prefill(c, tokens, lengths, B, commit_layers, C, committed_hidden, nullptr, hidden_dtype, committed_argmax, nullptr,
                        committed_argmax != nullptr, tol, flags, stats, summary, true, &seg);
+}
+
+namespace {
+bool rule_valid(const vl_bit_rule* r) {
+    const float f[] = {r->e_w, r->q_small, r->tau_large, r->pe_max, r->pm_min, r->pw_min, r->eps_max, r->q_small_min, r->z_large_max};
+    for (float v : f) if (v != v) return false;
+    return r->e_m >= 0 && r->step_log2 >= 0 && r->step_log2 <= 23;
+}
+}  // namespace
+
+int vl_set_bit_rule(vl_ctx* c, const vl_bit_rule* rule) {
+    if (!c) return VL_E_ARG;
+    if (rule && !rule_valid(rule)) return c->fail(VL_E_ARG, "bit rule: e_m must be >= 0, step_log2 within [0, 23], no field NaN");
+    c->has_rule = rule != nullptr;
+    if (rule) c->rule = *rule;
+    return VL_OK;
+}
+
+int vl_get_bit_stats(vl_ctx* c, int32_t ci, int64_t tok_begin, int64_t tok_end, vl_bit_stats* out) {
+    if (!c) return VL_E_ARG;
+    if (c->last_bits_c == 0) return c->fail(VL_E_ARG, "the most recent call ran no bit-aware rule");
+    if (ci < 0 || ci >= c->last_bits_c || tok_begin < 0 || tok_end < tok_begin || tok_end > c->last_n)
+        return c->fail(VL_E_ARG, "commit-layer index or token range outside the most recent verify call");
+    if (tok_end == tok_begin) return VL_OK;
+    if (!out) return c->fail(VL_E_ARG, "out is NULL");
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, hipMemcpyAsync(out, c->bit_stats + (int64_t)ci * c->last_n + tok_begin, (size_t)(tok_end - tok_begin) * sizeof(vl_bit_stats),
+                              hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return VL_OK;
 }
 
 int vl_prefill_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,
@@ -898,6 +937,20 @@ int vl_op_compare(vl_ctx* c, const float* h_hat, const void* committed, int32_t 
     if (N == 0) return VL_OK;
     HIP_TRY(c, hipSetDevice(c->device));
     launch_compare(h_hat, committed, hidden_dtype, N, c->cfg.d_model, tol->rel_l2, tol->max_abs, stats, nullptr, ok, c->stream);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return VL_OK;
+}
+
+int vl_op_compare_bits(vl_ctx* c, const float* h_hat, const void* committed, int32_t hidden_dtype, int64_t N, const vl_tol* tol,
+                       const vl_bit_rule* rule, vl_tok_stats* stats, vl_bit_stats* bits, uint8_t* ok) {
+    if (!c) return VL_E_ARG;
+    if (N < 0 || (N > 0 && (!h_hat || !committed)) || !tol || !rule) return c->fail(VL_E_ARG, "bad pointer or N < 0");
+    if (hidden_dtype != VL_F32 && hidden_dtype != VL_BF16) return c->fail(VL_E_ARG, "hidden_dtype must be VL_F32 or VL_BF16");
+    if (!rule_valid(rule)) return c->fail(VL_E_ARG, "bit rule: e_m must be >= 0, step_log2 within [0, 23], no field NaN");
+    if (N == 0) return VL_OK;
+    HIP_TRY(c, hipSetDevice(c->device));
+    launch_compare(h_hat, committed, hidden_dtype, N, c->cfg.d_model, tol->rel_l2, tol->max_abs, stats, nullptr, ok, c->stream, rule, bits);
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return VL_OK;

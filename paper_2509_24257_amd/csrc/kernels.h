@@ -70,7 +70,8 @@ void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t l
 
 // ---- compare / argmax / flags (kernels_compare.hip) ------------------------------------------------
 void launch_compare(const float* h_hat, const void* committed, int hidden_dtype, int64_t rows, int d, float tol_rel,
-                    float tol_abs, vl_tok_stats* stats, uint8_t* ok_and, uint8_t* ok_set, hipStream_t s);
+                    float tol_abs, vl_tok_stats* stats, uint8_t* ok_and, uint8_t* ok_set, hipStream_t s,
+                    const vl_bit_rule* rule = nullptr, vl_bit_stats* bit_stats = nullptr);
 void launch_argmax(const float* logits, int64_t rows, int vocab, const int32_t* committed, float margin,
                    int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s);
 struct DevSummary { unsigned long long n_rejected, n_hidden_reject, n_token_reject; float max_rel, max_abs, mean_mae; };

@@ -25,17 +25,41 @@ template <> struct Load8<float> {
     }
 };
 
-template <typename TC>
+// Bit-aware counts of Section 7 ("Bit-aware statistical comparison") and of the offline battery of Appendix A.1,
+// taken in the same pass when BITS is set: both operands are canonical float32, split into exponent (bits 30..23)
+// and mantissa (bits 22..0) fields; per row
+//   exact          identical bit patterns
+//   exp_mismatch   exponent fields differ                                      (P_e  = exp_mismatch / d)
+//   mismatch_close among those, |Delta| <= e_w                                 (P_m  = mismatch_close / exp_mismatch)
+//   match_small    among equal exponents, mantissa fields <= mant_tol apart    (P_w  = match_small / (d - exp_mismatch))
+//   small / large  |Delta| <= q_small, |Delta| > tau_large                     (Q_small, Z_large)
+// and the acceptance rule P_e < pe_max, P_m > pm_min, P_w > pw_min, |mean Delta| <= eps_max, Q_small >= q_small_min,
+// Z_large <= z_large_max, each ratio test taken as count vs bound * size in fp32; a ratio over an empty set passes.
+struct BitParams {
+    float e_w, q_small, tau_large;
+    int mant_tol;                                  // e_m << step_log2, clamped to the largest mantissa distance
+    float pe_max, pm_min, pw_min, eps_max, q_small_min, z_large_max;
+};
+
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+template <typename TC, bool BITS>
 __global__ __launch_bounds__(256) void compare_kernel(const float* __restrict__ h_hat, const TC* __restrict__ h_star,
                                                       int64_t rows, int d, float tol_rel, float tol_abs,
                                                       vl_tok_stats* __restrict__ stats, uint8_t* __restrict__ ok_and,
-                                                      uint8_t* __restrict__ ok_set) {
+                                                      uint8_t* __restrict__ ok_set, BitParams bp,
+                                                      vl_bit_stats* __restrict__ bit_stats) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;                      // whole wave leaves together; no barrier below
     const float* a = h_hat + row * (int64_t)d;
     const TC* b = h_star + row * (int64_t)d;
     float e2 = 0.f, n2 = 0.f, e1 = 0.f, es = 0.f, emax = 0.f;
+    int c_exact = 0, c_mis = 0, c_close = 0, c_msmall = 0, c_small = 0, c_large = 0;
     const int chunks = d >> 3;
 #pragma unroll 4
     for (int c = lane; c < chunks; c += WAVE) {
@@ -50,6 +74,18 @@ __global__ __launch_bounds__(256) void compare_kernel(const float* __restrict__ 
             e1 += fabsf(dl);
             es += dl;
             emax = fmaxf(emax, fabsf(dl));        // fmaxf drops NaN; a NaN row is recovered from e2 below
+            if (BITS) {
+                const uint32_t ux = __float_as_uint(x[i]), uy = __float_as_uint(y[i]);
+                const bool mis = ((ux ^ uy) & 0x7F800000u) != 0;
+                const int md = abs((int)(ux & 0x7FFFFFu) - (int)(uy & 0x7FFFFFu));
+                const float ad = fabsf(dl);
+                c_exact += (ux == uy);
+                c_mis += mis;
+                c_close += mis && (ad <= bp.e_w);
+                c_msmall += !mis && (md <= bp.mant_tol);
+                c_small += (ad <= bp.q_small);
+                c_large += (ad > bp.tau_large);
+            }
         }
     }
     e2 = wave_sum(e2);
@@ -57,6 +93,14 @@ __global__ __launch_bounds__(256) void compare_kernel(const float* __restrict__ 
     e1 = wave_sum(e1);
     es = wave_sum(es);
     emax = wave_max(emax);
+    if (BITS) {
+        c_exact = wave_sum_i(c_exact);
+        c_mis = wave_sum_i(c_mis);
+        c_close = wave_sum_i(c_close);
+        c_msmall = wave_sum_i(c_msmall);
+        c_small = wave_sum_i(c_small);
+        c_large = wave_sum_i(c_large);
+    }
     if (lane == 0) {
         const float rel = sqrtf(e2) / fmaxf(sqrtf(n2), 1e-30f);
         if (e2 != e2) emax = e2;                  // NaN anywhere in the row -> max_abs is NaN
@@ -67,22 +111,45 @@ __global__ __launch_bounds__(256) void compare_kernel(const float* __restrict__ 
         st.mean_abs = e1 * inv_d;
         st.mean_signed = es * inv_d;
         if (stats) stats[row] = st;
-        const uint8_t ok = (rel <= tol_rel) && (emax <= tol_abs);   // NaN compares false -> reject
+        uint8_t ok = (rel <= tol_rel) && (emax <= tol_abs);         // NaN compares false -> reject
+        if (BITS) {
+            const float fd = (float)d, fm = (float)c_mis, fmatch = fd - fm;
+            const bool rule = (fm < bp.pe_max * fd) && (c_mis == 0 || (float)c_close > bp.pm_min * fm) &&
+                              (fmatch == 0.f || (float)c_msmall > bp.pw_min * fmatch) && (fabsf(st.mean_signed) <= bp.eps_max) &&
+                              ((float)c_small >= bp.q_small_min * fd) && ((float)c_large <= bp.z_large_max * fd);
+            vl_bit_stats bs;
+            bs.n_exact = c_exact;
+            bs.n_exp_mismatch = c_mis;
+            bs.n_mismatch_close = c_close;
+            bs.n_match_small = c_msmall;
+            bs.n_small = c_small;
+            bs.n_large = c_large;
+            bs.mean_signed = st.mean_signed;
+            bs.ok = rule ? 1u : 0u;
+            if (bit_stats) bit_stats[row] = bs;
+            ok = ok && rule;
+        }
         if (ok_and) ok_and[row] = ok_and[row] & ok;
         if (ok_set) ok_set[row] = ok;
     }
 }
 
 void launch_compare(const float* h_hat, const void* committed, int hidden_dtype, int64_t rows, int d, float tol_rel,
-                    float tol_abs, vl_tok_stats* stats, uint8_t* ok_and, uint8_t* ok_set, hipStream_t s) {
+                    float tol_abs, vl_tok_stats* stats, uint8_t* ok_and, uint8_t* ok_set, hipStream_t s,
+                    const vl_bit_rule* rule, vl_bit_stats* bit_stats) {
     if (rows <= 0) return;
     dim3 grid((unsigned)((rows + 3) / 4));
-    if (hidden_dtype == VL_BF16)
-        compare_kernel<bf16><<<grid, 256, 0, s>>>(h_hat, (const bf16*)committed, rows, d, tol_rel, tol_abs, stats, ok_and,
-                                                  ok_set);
-    else
-        compare_kernel<float><<<grid, 256, 0, s>>>(h_hat, (const float*)committed, rows, d, tol_rel, tol_abs, stats,
-                                                   ok_and, ok_set);
+    BitParams bp{};
+    if (rule) {
+        const long long tol = (long long)rule->e_m << rule->step_log2;
+        bp = BitParams{rule->e_w, rule->q_small, rule->tau_large, (int)(tol > 0x7FFFFF ? 0x7FFFFF : tol), rule->pe_max,
+                       rule->pm_min, rule->pw_min, rule->eps_max, rule->q_small_min, rule->z_large_max};
+    }
+#define VL_CMP(TC, BITS) compare_kernel<TC, BITS><<<grid, 256, 0, s>>>(h_hat, (const TC*)committed, rows, d, tol_rel, tol_abs, stats, \
+                                                                        ok_and, ok_set, bp, bit_stats)
+    if (hidden_dtype == VL_BF16) { if (rule) VL_CMP(bf16, true); else VL_CMP(bf16, false); }
+    else { if (rule) VL_CMP(float, true); else VL_CMP(float, false); }
+#undef VL_CMP
 }
 
 // ---------------------------------------------------------------- argmax + TokenMatch: one workgroup per row

@@ -30,6 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_the_header():
     assert C.sizeof(P.ModelCfg) == 13 * 4
     assert C.sizeof(P.Tol) == 12 and C.sizeof(P.TokStats) == 16
+    assert C.sizeof(P.BitRule) == 11 * 4 and C.sizeof(P.BitStats) == 8 * 4
     assert C.sizeof(P.Summary) == 4 * 8 + 5 * 4 + 4          # 4 bytes of tail padding to the int64 alignment
 
 

@@ -380,3 +380,111 @@ def test_segment_argument_errors_and_partial_weights(small_bf16):
         assert e.value.code == -2
     finally:
         ctx2.close()
+
+
+# ====================================================================================== bit-aware rule inside the verify pass
+BIT_PARAMS = dict(e_w=5e-2, e_m=7, step_log2=16, q_small=1e-5, tau_large=0.25)
+BIT_THRESH = dict(pe_max=0.15, pm_min=0.5, pw_min=0.7, eps_max=0.01, q_small_min=0.0, z_large_max=0.05)
+
+
+def bit_rule_struct():
+    b, t = BIT_PARAMS, BIT_THRESH
+    return P.BitRule(b["e_w"], b["e_m"], b["step_log2"], b["q_small"], b["tau_large"], t["pe_max"], t["pm_min"], t["pw_min"],
+                     t["eps_max"], t["q_small_min"], t["z_large_max"])
+
+
+def get_bits(ctx, c, n):
+    out = torch.zeros(n * 8, dtype=torch.int32, device=H.DEV)
+    ctx.vl_get_bit_stats(c, 0, n, out.data_ptr())
+    a = out.cpu().numpy().reshape(n, 8)
+    return {"n_exact": a[:, 0], "n_exp_mismatch": a[:, 1], "n_mismatch_close": a[:, 2], "n_match_small": a[:, 3],
+            "n_small": a[:, 4], "n_large": a[:, 5], "ok": a[:, 7].astype(bool)}
+
+
+def test_small_bf16_bit_rule_flags_match_oracle(small_bf16):
+    """Thresholds sit well inside the gap between honest noise and tampering (checked below on the oracle side), so the
+    verdicts are unique although the GPU's counts differ from the oracle's by the bf16 noise of its states."""
+    ctx, om, wl, x = small_bf16
+    n = wl.n_tokens
+    hid, z = O.prefill(om, x, wl.lengths, wl.commit_layers)
+    committed = np.stack([hid[l] for l in wl.commit_layers]).astype(np.float32)
+    pos = synth.tamper_positions(wl)
+    com_st = H.stored(synth.tamper_hidden(wl, committed, pos), "bf16")
+    cam = O.argmax_lowest(z).astype(np.int32)
+    expect = np.ones(n, np.uint8)
+    expect[pos] = 0
+    honest = expect.astype(bool)
+    ref = O.verify(om, x, wl.lengths, wl.commit_layers, com_st, cam, wl.tol_rel_l2, wl.tol_max_abs, wl.tol_logit_margin,
+                   bit_params=BIT_PARAMS, bit_thresholds=BIT_THRESH)
+    np.testing.assert_array_equal(ref["flags"], expect)
+    # what a bf16 implementation's own noise does to the counts, from the oracle's bf16-operand model
+    ref_fmt = O.verify(H.oracle_model(wl.model, operand_dtype="bf16"), x, wl.lengths, wl.commit_layers, com_st, cam, wl.tol_rel_l2,
+                       wl.tol_max_abs, wl.tol_logit_margin, bit_params=BIT_PARAMS, bit_thresholds=BIT_THRESH)
+    np.testing.assert_array_equal(ref_fmt["flags"], expect)
+    say("small bf16 verify with the bit-aware rule switched on")
+    ctx.vl_set_bit_rule(bit_rule_struct())
+    try:
+        flags, stats, sm = H.run_verify(ctx, wl, x, com_st, cam)
+        np.testing.assert_array_equal(flags, ref["flags"])
+        assert sm["n_rejected"] == len(pos) and sm["n_hidden_reject"] == len(pos)
+        d = wl.model.d_model
+        for c in range(len(wl.commit_layers)):
+            g, r = get_bits(ctx, c, n), ref_fmt["stats"][c]["bits"]
+            np.testing.assert_array_equal(g["ok"], ref["stats"][c]["bit_ok"])
+            pe_g, pe_r = g["n_exp_mismatch"][honest] / d, r["n_exp_mismatch"][honest] / d
+            pw_g = g["n_match_small"][honest] / (d - g["n_exp_mismatch"][honest])
+            pw_r = r["n_match_small"][honest] / (d - r["n_exp_mismatch"][honest])
+            print(f"  layer {wl.commit_layers[c]}: honest P_e mean {pe_g.mean():.4f} (bf16-operand oracle {pe_r.mean():.4f}), "
+                  f"P_w mean {pw_g.mean():.4f} ({pw_r.mean():.4f}); tampered P_e min {g['n_exp_mismatch'][~honest].min() / d:.3f}", flush=True)
+            assert abs(pe_g.mean() - pe_r.mean()) <= 0.3 * pe_r.mean() and abs(pw_g.mean() - pw_r.mean()) <= 0.03
+            assert pe_g.max() < 0.8 * BIT_THRESH["pe_max"] and pw_g.min() > BIT_THRESH["pw_min"] + 0.05
+            assert (g["n_exp_mismatch"][~honest] / d).min() > 3 * BIT_THRESH["pe_max"]
+        say("rule off again: the counts of the previous call are gone, the flags come from the tolerance test alone")
+        ctx.vl_set_bit_rule(None)
+        flags2, _, _ = H.run_verify(ctx, wl, x, com_st, cam)
+        np.testing.assert_array_equal(flags2, expect)
+        with pytest.raises(P.VerilLMError) as e:
+            ctx.vl_get_bit_stats(0, 0, n, 0)
+        assert e.value.code == -1
+        with pytest.raises(P.VerilLMError) as e:
+            ctx.vl_set_bit_rule(P.BitRule(1e-2, -1, 0, 1e-5, 0.1, 0.05, 0.75, 0.8, 0.01, 0.0, 1.0))
+        assert e.value.code == -1
+    finally:
+        ctx.vl_set_bit_rule(None)
+
+
+def test_small_bf16_bit_rule_catches_a_coarsened_model_inside_the_norm_tolerance(small_bf16):
+    """Appendix A.1 (precision-degradation attack): the inferencer runs the same model with every matrix cut to 4 mantissa
+    bits.  Its states stay within the relative-L2 tolerance at every position, so the tolerance test alone accepts; the
+    mantissa statistics give it away.  Both sides must agree on every flag."""
+    ctx, om, wl, x = small_bf16
+    m = wl.model
+
+    def coarse(w):
+        mant, ex = np.frexp(synth.bf16_bits_to_f32(w).astype(np.float64))
+        return synth.f32_to_bf16_bits(np.ldexp(np.round(mant * 32) / 32, ex).astype(np.float32))
+
+    ov = {(k, l): coarse(synth.weight(m, k, l)) for l in range(m.n_layers)
+          for k in (synth.WQ, synth.WK, synth.WV, synth.WO, synth.W_GATE, synth.W_UP, synth.W_DOWN)}
+    hq, _ = O.prefill(H.oracle_model(m, override=ov), x, wl.lengths, wl.commit_layers, want_logits=False)
+    com_st = H.stored(np.stack([hq[l] for l in wl.commit_layers]).astype(np.float32), "bf16")
+    plain = O.verify(om, x, wl.lengths, wl.commit_layers, com_st, None, wl.tol_rel_l2, wl.tol_max_abs, wl.tol_logit_margin)
+    ruled = O.verify(om, x, wl.lengths, wl.commit_layers, com_st, None, wl.tol_rel_l2, wl.tol_max_abs, wl.tol_logit_margin,
+                     bit_params=BIT_PARAMS, bit_thresholds=BIT_THRESH)
+    assert plain["flags"].all() and max(s["rel_l2"].max() for s in plain["stats"]) < 0.9 * wl.tol_rel_l2
+    assert not ruled["flags"].any()
+    say("coarsened inferencer: tolerance test alone")
+    flags, stats, _ = H.run_verify(ctx, wl, x, com_st, None)
+    np.testing.assert_array_equal(flags, plain["flags"])
+    say("coarsened inferencer: with the bit-aware rule")
+    ctx.vl_set_bit_rule(bit_rule_struct())
+    try:
+        flags, _, sm = H.run_verify(ctx, wl, x, com_st, None)
+        np.testing.assert_array_equal(flags, ruled["flags"])
+        assert sm["n_rejected"] == wl.n_tokens
+        last = get_bits(ctx, len(wl.commit_layers) - 1, wl.n_tokens)
+        pw = last["n_match_small"] / (m.d_model - last["n_exp_mismatch"])
+        print(f"  last committed layer: P_w max {pw.max():.3f} (bound {BIT_THRESH['pw_min']})", flush=True)
+        assert pw.max() < BIT_THRESH["pw_min"] - 0.03
+    finally:
+        ctx.vl_set_bit_rule(None)

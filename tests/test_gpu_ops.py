@@ -87,6 +87,69 @@ def test_compare_is_bit_reproducible(ctx_small_bf16):
     assert outs[0] == outs[1] == outs[2]
 
 
+# ------------------------------------------------------------------ bit-aware counts and rule (Section 7, Appendix A.1)
+BIT_KEYS = ("n_exact", "n_exp_mismatch", "n_mismatch_close", "n_match_small", "n_small", "n_large")
+
+
+def bits_from_dev(t, n):
+    a = t.cpu().numpy().reshape(n, 8)
+    out = {k: a[:, i].astype(np.int64) for i, k in enumerate(BIT_KEYS)}
+    out["mean_signed"] = a[:, 6].copy().view(np.float32)
+    out["ok"] = a[:, 7].astype(bool)
+    return out
+
+
+@pytest.mark.parametrize("dtype,step_log2,e_m", [("f32", 0, 7), ("bf16", 16, 7), ("f32", 12, 3), ("bf16", 23, 1)])
+@pytest.mark.parametrize("n", [1, 130, 1027])
+def test_compare_bits_counts_are_bit_exact(ctx_small_bf16, dtype, step_log2, e_m, n):
+    ctx, m = ctx_small_bf16
+    d = m.d_model
+    say(f"compare_bits dtype={dtype} step_log2={step_log2} e_m={e_m} n={n}")
+    rng = np.random.default_rng(1000 * n + step_log2)
+    h = (rng.standard_normal((n, d)) * np.exp(rng.uniform(-2, 2, (n, 1)))).astype(np.float32)
+    # rows of different character: cross-device-like relative noise of several sizes, a constant offset (mean shift), a
+    # scaled copy (every exponent off by one), exact copies, coarse noise
+    kind = rng.integers(0, 6, n)
+    noise = np.choose(kind, [1e-7, 1e-4, 3e-3, 0.0, 0.0, 0.3])[:, None]
+    star = (h * (1 + noise * rng.standard_normal((n, d)))).astype(np.float32)
+    star[kind == 3] += np.float32(0.05)
+    star[kind == 4] *= np.float32(2.0)
+    if n > 100:
+        star[5, 3], star[6, 0], h[7, 9] = np.nan, np.inf, np.nan
+        star[8, :40] = 0.0
+        h[9, :40] = 0.0
+        star[9, :20] = -0.0
+        h[10, 0], star[10, 0], h[10, 1], star[10, 1] = 1e-40, 3e-40, 1e-38, 1.3e-38      # denormals, and one next to the border
+    st = H.stored(star, dtype)
+    rule = P.BitRule(1e-2, e_m, step_log2, 1e-5, 0.1, 0.05, 0.75, 0.80, 0.01, 0.0, 0.3)
+    tol = P.Tol(math.inf, math.inf, 0.0)                      # the tolerance test is wide open: `ok` is the rule alone
+    d_h, d_s = H.to_dev(h), H.to_dev(st)
+    d_stats = torch.zeros(n * 4, dtype=torch.float32, device=H.DEV)
+    d_bits = torch.zeros(n * 8, dtype=torch.int32, device=H.DEV)
+    d_ok = torch.full((n,), 9, dtype=torch.uint8, device=H.DEV)
+    ctx.vl_op_compare_bits(d_h.data_ptr(), d_s.data_ptr(), H.hidden_dtype_code(dtype), n, tol, rule, d_stats.data_ptr(),
+                           d_bits.data_ptr(), d_ok.data_ptr())
+    got = bits_from_dev(d_bits, n)
+    ref = O.bit_compare(h, st, 1e-2, e_m, step_log2, 1e-5, 0.1)
+    for k in BIT_KEYS:
+        np.testing.assert_array_equal(got[k], ref[k], err_msg=k)
+    cmp_ref = O.compare_hidden(h, st, math.inf, math.inf)
+    want = O.bit_rule(ref, cmp_ref["mean_signed"], 0.05, 0.75, 0.80, 0.01, 0.0, 0.3)
+    # the mean is summed in another order on the GPU: leave out rows whose |mean| sits within rounding of the bound
+    with np.errstate(invalid="ignore"):
+        clear = ~(np.abs(np.abs(cmp_ref["mean_signed"]) - 0.01) < 1e-5)
+    np.testing.assert_array_equal(got["ok"][clear], want[clear])
+    nanrow = np.isnan(cmp_ref["mean_signed"])               # NaN never passes a <= / > test, so such rows fail
+    np.testing.assert_array_equal(d_ok.cpu().numpy().astype(bool)[clear & ~nanrow], want[clear & ~nanrow])
+    assert not d_ok.cpu().numpy()[nanrow].any()
+    if n > 100:
+        assert want.any() and (~want).any()                 # the mix really exercises both verdicts
+    with pytest.raises(P.VerilLMError) as e:
+        ctx.vl_op_compare_bits(d_h.data_ptr(), d_s.data_ptr(), H.hidden_dtype_code(dtype), n, tol,
+                               P.BitRule(1e-2, 7, 24, 1e-5, 0.1, 0.05, 0.75, 0.8, 0.01, 0.0, 1.0), 0, d_bits.data_ptr(), 0)
+    assert e.value.code == -1
+
+
 # ------------------------------------------------------------------ argmax + TokenMatch
 @pytest.mark.parametrize("vocab,n", [(1000, 37), (4096, 5), (128256, 9), (1001, 6)])
 def test_argmax_and_token_check_match_oracle(vocab, n):
