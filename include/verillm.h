@@ -274,7 +274,8 @@ int vl_profile_read(vl_ctx* ctx, double* ms, int64_t* launches);
 /* ---- single operations, exposed so that each kernel can be checked on its own ------------------ */
 
 /* C[M,N] = A[M,K] * W[N,K]^T on the matrix cores: A, W bf16 [device], fp32 accumulate, `out` bf16 when
-   out_dtype == VL_BF16 else float32.  K must be a multiple of 64; M, N >= 1. */
+   out_dtype == VL_BF16 else float32.  K must be a multiple of 64; M, N >= 1.  M <= 64 rows take the weight-streaming
+   kernel of the token-by-token path, larger M the 256 x 256 tile kernel of the prefill. */
 int vl_op_gemm_bf16(vl_ctx* ctx, const void* A, const void* W, void* out, int32_t out_dtype,
                     int32_t M, int32_t N, int32_t K);
 
@@ -283,6 +284,15 @@ int vl_op_gemm_bf16(vl_ctx* ctx, const void* A, const void* W, void* out, int32_
    the key heads, then the value heads (rotary embedding already applied to queries and keys).
    out [device] bf16 [N][n_q_heads * head_dim].  lengths [host] int32 [B]. */
 int vl_op_attention_bf16(vl_ctx* ctx, const void* qkv, const int32_t* lengths, int32_t B, void* out);
+
+/* The attention of one token-by-token step (Section 5.5) on its own: query row r attends to the n_keys[r] cached
+   positions first_row[r] .. first_row[r] + n_keys[r] - 1 (its own key is the last of them).  bf16 contexts with
+   head_dim 64 or 128 and n_q_heads / n_kv_heads in {1, 2, 4, 8}.
+   q [device] bf16 [rows][n_q_heads*head_dim] (rotary embedding already applied); k_cache, v_cache [device] bf16
+   [cache_rows][n_kv_heads*head_dim]; first_row, n_keys [host] int32 [rows], n_keys >= 1; out [device] bf16
+   [rows][n_q_heads*head_dim].  VL_E_ARG if a key range leaves the cache. */
+int vl_op_attention_decode_bf16(vl_ctx* ctx, const void* q, const void* k_cache, const void* v_cache, int64_t cache_rows,
+                                const int32_t* first_row, const int32_t* n_keys, int32_t rows, void* out);
 
 /* Compare stage alone (Section 5.7): h_hat [device] float32 [N][d_model] against committed [device]
    [N][d_model] in hidden_dtype; stats [device] out [N]; ok [device] out uint8 [N]. */

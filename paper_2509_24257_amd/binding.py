@@ -17,7 +17,7 @@ _STATUS = {0: "VL_OK", -1: "VL_E_ARG", -2: "VL_E_WEIGHTS", -3: "VL_E_CAPACITY", 
 EXPORTS = ["vl_plan_memory", "vl_create", "vl_load_weights", "vl_destroy", "vl_last_error", "vl_verify_prefill",
            "vl_verify_segment", "vl_prefill_commit", "vl_decode_commit", "vl_get_logits", "vl_get_argmax",
            "vl_set_bit_rule", "vl_get_bit_stats", "vl_profile_enable", "vl_profile_read", "vl_op_gemm_bf16",
-           "vl_op_attention_bf16", "vl_op_compare", "vl_op_compare_bits", "vl_op_argmax"]
+           "vl_op_attention_bf16", "vl_op_attention_decode_bf16", "vl_op_compare", "vl_op_compare_bits", "vl_op_argmax"]
 
 
 STAGES = ["embed", "norm", "qkv_gemm", "rope", "attention", "o_gemm", "gateup_gemm", "down_gemm", "compare", "lm_gemm",
@@ -106,6 +106,7 @@ def load_library():
     lib.vl_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.vl_op_gemm_bf16.argtypes = [vp, vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.vl_op_attention_bf16.argtypes = [vp, vp, i32p, C.c_int32, vp]
+    lib.vl_op_attention_decode_bf16.argtypes = [vp, vp, vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
     lib.vl_op_compare.argtypes = [vp, vp, vp, C.c_int32, C.c_int64, C.POINTER(Tol), vp, vp]
     lib.vl_op_argmax.argtypes = [vp, vp, C.c_int64, vp, C.c_float, vp, vp, vp]
     for name in EXPORTS:
@@ -235,6 +236,14 @@ class Context:
     def vl_op_attention_bf16(self, qkv: int, lengths: Sequence[int], out: int):
         la, b = _i32(lengths)
         self._check(lib().vl_op_attention_bf16(self._h, C.c_void_p(qkv), la, b, C.c_void_p(out)))
+
+    def vl_op_attention_decode_bf16(self, q: int, k_cache: int, v_cache: int, cache_rows: int, first_row: Sequence[int],
+                                    n_keys: Sequence[int], out: int):
+        fa, rows = _i32(first_row)
+        na, _ = _i32(n_keys)
+        self._check(lib().vl_op_attention_decode_bf16(self._h, C.c_void_p(q or None), C.c_void_p(k_cache or None),
+                                                      C.c_void_p(v_cache or None), int(cache_rows), fa, na, rows,
+                                                      C.c_void_p(out or None)))
 
     def vl_op_compare(self, h_hat: int, committed: int, hidden_dtype: int, n: int, tol: Tol, stats: int, ok: int):
         self._check(lib().vl_op_compare(self._h, C.c_void_p(h_hat or None), C.c_void_p(committed or None), int(hidden_dtype),

@@ -292,10 +292,11 @@ bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, bool want_tile
     return true;
 }
 
-// bf16 models: every GEMM runs on the matrix cores (for the few rows of a decode step the kernel is bound by
-// streaming the weight tiles, which is what a decode step has to do anyway).  fp32 models: vector-ALU GEMM.
+// bf16 models: every GEMM runs on the matrix cores; up to 64 rows (a decode step) take the weight-streaming kernel,
+// more rows the 256 x 256 tile kernel.  fp32 models: vector-ALU GEMM.
 void gemm(vl_ctx* c, const void* A, const void* W, int M, int N, int K, int epi, void* out) {
-    if (c->bf16) launch_gemm_mfma(A, W, M, N, K, epi, out, c->stream);
+    if (c->bf16 && M <= GEMM_SKINNY_MAX_M) launch_gemm_skinny(A, W, M, N, K, epi, out, c->stream);
+    else if (c->bf16) launch_gemm_mfma(A, W, M, N, K, epi, out, c->stream);
     else launch_gemm_simple(A, W, c->cfg.dtype, M, N, K, epi, out, (int)c->plan.ib, c->stream);
 }
 
@@ -344,8 +345,12 @@ void block_decode(vl_ctx* c, int l, int rows, const int32_t* pos, const int32_t*
     gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
     launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
     launch_kv_store(c->qkv, m.dtype, c->kcache + lo, c->vcache + lo, cache_row, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
-    launch_attn_rowwise(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, m.dtype, rows,
-                        m.n_q_heads, m.n_kv_heads, m.head_dim, s);
+    if (c->bf16 && attn_decode_supported(m.n_q_heads, m.n_kv_heads, m.head_dim))
+        launch_attn_decode(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, rows, m.n_q_heads,
+                           m.n_kv_heads, m.head_dim, s);
+    else
+        launch_attn_rowwise(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, m.dtype, rows,
+                            m.n_q_heads, m.n_kv_heads, m.head_dim, s);
     gemm(c, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid);
     launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s);
     gemm(c, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act);
@@ -895,7 +900,8 @@ int vl_op_gemm_bf16(vl_ctx* c, const void* A, const void* W, void* out, int32_t 
     if (M < 1 || N < 1 || K < 64 || K % 64) return c->fail(VL_E_ARG, "need M, N >= 1 and K a positive multiple of 64");
     if (out_dtype != VL_F32 && out_dtype != VL_BF16) return c->fail(VL_E_ARG, "out_dtype must be VL_F32 or VL_BF16");
     HIP_TRY(c, hipSetDevice(c->device));
-    launch_gemm_mfma(A, W, M, N, K, out_dtype == VL_BF16 ? EPI_STORE : EPI_STORE_F32, out, c->stream);
+    if (M <= GEMM_SKINNY_MAX_M) launch_gemm_skinny(A, W, M, N, K, out_dtype == VL_BF16 ? EPI_STORE : EPI_STORE_F32, out, c->stream);
+    else launch_gemm_mfma(A, W, M, N, K, out_dtype == VL_BF16 ? EPI_STORE : EPI_STORE_F32, out, c->stream);
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return VL_OK;
@@ -924,6 +930,38 @@ int vl_op_attention_bf16(vl_ctx* c, const void* qkv, const int32_t* lengths, int
     if (rc) return rc;
     launch_transpose_v(qkv, c->vt, bi.vt_col, n, m.n_q_heads, m.n_kv_heads, m.head_dim, c->plan.vt_ld, c->stream);
     launch_attn_mfma(qkv, n, c->vt, c->plan.vt_ld, bi.tiles, bi.n_tiles, out, m.n_q_heads, m.n_kv_heads, m.head_dim, c->stream);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return VL_OK;
+}
+
+int vl_op_attention_decode_bf16(vl_ctx* c, const void* q, const void* k_cache, const void* v_cache, int64_t cache_rows,
+                                const int32_t* first_row, const int32_t* n_keys, int32_t rows, void* out) {
+    if (!c) return VL_E_ARG;
+    if (!c->bf16) return c->fail(VL_E_ARG, "the context is not a bf16 model");
+    const vl_model_cfg& m = c->cfg;
+    if (!attn_decode_supported(m.n_q_heads, m.n_kv_heads, m.head_dim))
+        return c->fail(VL_E_ARG, "needs head_dim 64 or 128 and n_q_heads / n_kv_heads in {1, 2, 4, 8}");
+    if (rows < 0 || (rows > 0 && (!q || !k_cache || !v_cache || !first_row || !n_keys || !out)))
+        return c->fail(VL_E_ARG, "NULL argument or rows < 0");
+    for (int r = 0; r < rows; ++r)
+        if (n_keys[r] < 1 || first_row[r] < 0 || (int64_t)first_row[r] + n_keys[r] > cache_rows)
+            return c->fail(VL_E_ARG, fmt("row %d: keys [%d, %d + %d) outside the cache of %lld rows", r, first_row[r], first_row[r],
+                                         n_keys[r], (long long)cache_rows));
+    if (rows == 0) return VL_OK;
+    HIP_TRY(c, hipSetDevice(c->device));
+    Stage st(c->h_idx, c->d_idx, c->plan.stage_ints);
+    int32_t *h0, *d0, *hp, *dp;
+    if (!st.take(rows, &h0, &d0) || !st.take(rows, &hp, &dp)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    for (int r = 0; r < rows; ++r) {
+        h0[r] = first_row[r];
+        hp[r] = n_keys[r] - 1;                                  // position of the query = index of its last key
+    }
+    int rc = upload_stage(c, st);
+    if (rc) return rc;
+    const int64_t kvd = (int64_t)m.n_kv_heads * m.head_dim;
+    launch_attn_decode(q, (int64_t)m.n_q_heads * m.head_dim, k_cache, v_cache, kvd, d0, dp, out, rows, m.n_q_heads, m.n_kv_heads,
+                       m.head_dim, c->stream);
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return VL_OK;

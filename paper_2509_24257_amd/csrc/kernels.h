@@ -51,6 +51,11 @@ void launch_gemm_simple(const void* A, const void* W, int dtype, int M, int N, i
 // rows and needs N % 64 == 0.
 void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s);
 
+// ---- bf16 weight-streaming GEMM for M <= 64 rows (kernels_gemm_skinny.hip) --------------------------
+// Same contract; K % 32 == 0; EPI_SWIGLU needs N % 64 == 0.
+constexpr int GEMM_SKINNY_MAX_M = 64;
+void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s);
+
 // ---- attention ------------------------------------------------------------------------------------
 // One wave per (query row, query head), online softmax over keys 0..npos[row].
 //   q    : [rows][q_stride] elements, head j at offset j*hd
@@ -58,6 +63,13 @@ void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi
 void launch_attn_rowwise(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                          const int32_t* kv_row0, const int32_t* npos, void* out, int dtype, int64_t rows, int hq,
                          int hkv, int hd, hipStream_t s);
+
+// bf16, one workgroup per (query row, KV head), all query heads of the group together (kernels_attn_decode.hip).
+// Same addressing as launch_attn_rowwise; needs head_dim 64 or 128 and Hq / Hkv in {1, 2, 4, 8}.
+bool attn_decode_supported(int hq, int hkv, int hd);
+void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
+                        const int32_t* kv_row0, const int32_t* npos, void* out, int64_t rows, int hq, int hkv, int hd,
+                        hipStream_t s);
 // Causal GQA flash attention on the matrix cores over packed sequences.
 //   qkv bf16 [N][(hq+2hkv)*hd], vt bf16 [hkv][hd][ldv] (values transposed, column = vt column of the token),
 //   tiles: host-built work list (see engine), out bf16 [N][hq*hd].

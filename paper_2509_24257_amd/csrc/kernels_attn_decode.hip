@@ -1,0 +1,167 @@
+// Attention of the token-by-token path (Section 5.5): one query position per live sequence against that sequence's
+// KV cache.  One workgroup (8 waves) per (query row, KV head); the G = Hq / Hkv query heads that share the KV head are
+// processed together, so every cached key and value is read once.
+//
+//   keys    : walked 64 at a time, block kb by wave kb % 8.  A key row (head_dim bf16) is read by head_dim/8 adjacent
+//             lanes, 16 bytes each, so a load instruction covers whole rows; each lane multiplies its 8 channels with
+//             the matching 8 query channels it keeps in registers, and a butterfly over the lanes of a row completes
+//             the dot product.  After head_dim/8 such passes lane l holds the score of key
+//             (l % LPK) * KPP + l / LPK of the block (LPK lanes per key, KPP keys per pass).
+//   softmax : online, per wave, in fp32 (running maximum and sum per query head).
+//   values  : per key one coalesced row read (lane l owns channels l*DPL .. +DPL-1); the key's probability is
+//             broadcast from the lane that holds it.
+//   combine : the eight waves' (max, sum, weighted values) meet in LDS and are merged in wave order.
+#include "common.h"
+#include "kernels.h"
+
+namespace vl {
+
+constexpr int AD_THREADS = 512;
+constexpr int AD_WAVES = 8;
+
+template <int G, int HD>
+__global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __restrict__ q, int64_t q_stride,
+                                                                 const bf16* __restrict__ k, const bf16* __restrict__ v,
+                                                                 int64_t kv_stride, const int32_t* __restrict__ kv_row0,
+                                                                 const int32_t* __restrict__ npos, bf16* __restrict__ out,
+                                                                 int hq, float scale) {
+    constexpr int LPK = HD / 8;                                 // lanes per key row
+    constexpr int KPP = WAVE / LPK;                             // keys per pass
+    constexpr int DPL = HD / WAVE;                              // value channels per lane
+    __shared__ float part_o[AD_WAVES][G][HD];
+    __shared__ float part_m[AD_WAVES][G], part_l[AD_WAVES][G];
+    const int64_t row = blockIdx.x;
+    const int kvh = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nkeys = npos[row] + 1;
+    const int64_t base = (int64_t)kv_row0[row];
+    const int sub = lane % LPK, kin = lane / LPK;               // 16-byte piece of a row, key within a pass
+
+    float qr[G][8];                                             // this lane's 8 channels of every query head, pre-scaled
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const bf16x8 t = *(const bf16x8*)(q + row * q_stride + (int64_t)(kvh * G + g) * HD + sub * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) qr[g][i] = (float)t[i] * scale;
+    }
+    float m[G], l[G], o[G][DPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) o[g][i] = 0.f;
+    }
+
+    const int nblocks = (nkeys + WAVE - 1) / WAVE;
+    for (int kb = wave; kb < nblocks; kb += AD_WAVES) {
+        const int t0 = kb * WAVE;
+        // ---- scores: pass j covers keys t0 + j*KPP .. + KPP-1; rows past the last key re-read it and are masked below
+        float sc[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) sc[g] = -INFINITY;
+#pragma unroll 4
+        for (int j = 0; j < LPK; ++j) {
+            const int t = t0 + j * KPP + kin;
+            const bf16x8 kv = *(const bf16x8*)(k + (base + min(t, nkeys - 1)) * kv_stride + (int64_t)kvh * HD + sub * 8);
+            float kf[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) kf[i] = (float)kv[i];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) d = fmaf(qr[g][i], kf[i], d);
+#pragma unroll
+                for (int s = LPK / 2; s > 0; s >>= 1) d += __shfl_xor(d, s, WAVE);
+                if (sub == j) sc[g] = (t < nkeys) ? d : -INFINITY;
+            }
+        }
+        // ---- online softmax; lane `lane` now holds key t0 + sub*KPP + kin
+        float p[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float mnew = fmaxf(m[g], wave_max(sc[g]));    // finite: the block holds at least one real key
+            p[g] = __expf(sc[g] - mnew);                        // exp(-inf) = 0 for masked keys
+            const float corr = __expf(m[g] - mnew);
+            l[g] = l[g] * corr + wave_sum(p[g]);
+            m[g] = mnew;
+#pragma unroll
+            for (int i = 0; i < DPL; ++i) o[g][i] *= corr;
+        }
+        // ---- weighted values, keys in order
+        const int cnt = min(WAVE, nkeys - t0);
+        const bf16* vp = v + (base + t0) * kv_stride + (int64_t)kvh * HD + lane * DPL;
+#pragma unroll 4
+        for (int jj = 0; jj < cnt; ++jj) {
+            float vf[DPL];
+            if (DPL == 1) {
+                vf[0] = (float)vp[(int64_t)jj * kv_stride];
+            } else {
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bf16x2 t = *(const bf16x2*)(vp + (int64_t)jj * kv_stride);
+                vf[0] = (float)t[0];
+                vf[DPL - 1] = (float)t[1];
+            }
+            const int src = (jj % KPP) * LPK + jj / KPP;        // the lane that holds key jj's probability
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[g]), src));
+#pragma unroll
+                for (int i = 0; i < DPL; ++i) o[g][i] = fmaf(pj, vf[i], o[g][i]);
+            }
+        }
+    }
+    // ---- merge the waves (a wave that had no block contributes max = -inf, sum = 0)
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (lane == 0) { part_m[wave][g] = m[g]; part_l[wave][g] = l[g]; }
+#pragma unroll
+        for (int i = 0; i < DPL; ++i) part_o[wave][g][lane * DPL + i] = o[g][i];
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < G * HD; e += AD_THREADS) {
+        const int g = e / HD, d = e % HD;
+        float mx = part_m[0][g];                                // wave 0 always owns block 0
+#pragma unroll
+        for (int w = 1; w < AD_WAVES; ++w) mx = fmaxf(mx, part_m[w][g]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < AD_WAVES; ++w) {
+            const float f = __expf(part_m[w][g] - mx);
+            num = fmaf(part_o[w][g][d], f, num);
+            den = fmaf(part_l[w][g], f, den);
+        }
+        out[row * (int64_t)hq * HD + (int64_t)(kvh * G + g) * HD + d] = (bf16)(num / den);
+    }
+}
+
+bool attn_decode_supported(int hq, int hkv, int hd) {
+    const int g = hkv > 0 ? hq / hkv : 0;
+    return (hd == 64 || hd == 128) && hq == g * hkv && (g == 1 || g == 2 || g == 4 || g == 8);
+}
+
+template <int G>
+static void launch_g(const bf16* q, int64_t q_stride, const bf16* k, const bf16* v, int64_t kv_stride, const int32_t* kv_row0,
+                     const int32_t* npos, bf16* out, int64_t rows, int hq, int hkv, int hd, hipStream_t s) {
+    const float scale = 1.0f / sqrtf((float)hd);
+    dim3 grid((unsigned)rows, (unsigned)hkv);
+    if (hd == 64)
+        attn_decode_kernel<G, 64><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale);
+    else
+        attn_decode_kernel<G, 128><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale);
+}
+
+void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
+                        const int32_t* kv_row0, const int32_t* npos, void* out, int64_t rows, int hq, int hkv, int hd,
+                        hipStream_t s) {
+    if (rows <= 0) return;
+    const bf16 *qq = (const bf16*)q, *kk = (const bf16*)k, *vv = (const bf16*)v;
+    switch (hq / hkv) {
+        case 1: launch_g<1>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
+        case 2: launch_g<2>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
+        case 4: launch_g<4>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
+        default: launch_g<8>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
+    }
+}
+
+}  // namespace vl

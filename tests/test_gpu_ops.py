@@ -195,7 +195,10 @@ def test_argmax_and_token_check_match_oracle(vocab, n):
 
 # ------------------------------------------------------------------ bf16 matrix-core GEMM
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (300, 200, 128), (1, 1, 64), (1000, 520, 192), (513, 257, 4096),
-                                   (2048, 1536, 512)])
+                                   (2048, 1536, 512), (65, 520, 192),
+                                   # M <= 64: the weight-streaming kernel of the token-by-token path
+                                   (8, 6144, 4096), (16, 4096, 14336), (17, 1000, 256), (33, 130, 192), (64, 4096, 4096),
+                                   (3, 31, 64), (48, 33, 320)])
 @pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
 def test_gemm_bf16_matches_float64_product(ctx_small_bf16, M, N, K, out_dtype):
     ctx, _ = ctx_small_bf16
@@ -263,3 +266,38 @@ def test_attention_hd128_gqa4_matches_oracle(ctx_hd128, lengths):
     ctx, m = ctx_hd128
     say(f"attention hd128 lengths={lengths}")
     assert _attention_case(ctx, m, lengths, 2) < 3e-2
+
+
+# ------------------------------------------------------------------ attention of the token-by-token path
+@pytest.mark.parametrize("hq,hkv,hd", [(4, 4, 64), (4, 2, 64), (8, 2, 128), (32, 8, 128), (8, 1, 128), (16, 2, 64)])
+def test_decode_attention_matches_oracle(hq, hkv, hd):
+    say(f"decode attention hq={hq} hkv={hkv} hd={hd}")
+    m = synth.small_model("bf16", n_layers=1, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, d_model=256)
+    ctx = P.Context(H.c_cfg(m, 256, 16, 256), 0, 0)        # op calls need no weights
+    try:
+        rng = np.random.default_rng(hq * 100 + hkv * 10 + hd)
+        n_keys = [1, 2, 63, 64, 65, 129, 512, 513, 1000, 3000]          # one query row per entry, caches back to back
+        first = np.concatenate([[0], np.cumsum(n_keys)[:-1]]).astype(np.int64) + 7          # and not at row 0
+        cache_rows = int(first[-1] + n_keys[-1] + 5)
+        kvd = hkv * hd
+        k_bits = synth.f32_to_bf16_bits((rng.standard_normal((cache_rows, kvd)) * 1.5).astype(np.float32))
+        v_bits = synth.f32_to_bf16_bits(rng.standard_normal((cache_rows, kvd)).astype(np.float32))
+        q_bits = synth.f32_to_bf16_bits((rng.standard_normal((len(n_keys), hq * hd)) * 1.5).astype(np.float32))
+        d_q, d_k, d_v = H.to_dev(q_bits), H.to_dev(k_bits), H.to_dev(v_bits)
+        d_o = torch.zeros((len(n_keys), hq * hd), dtype=torch.int16, device=H.DEV)
+        ctx.vl_op_attention_decode_bf16(d_q.data_ptr(), d_k.data_ptr(), d_v.data_ptr(), cache_rows, first.tolist(), n_keys, d_o.data_ptr())
+        got = O.upcast(H.bits_from_dev(d_o)).reshape(len(n_keys), hq, hd)
+        kf, vf, qf = O.upcast(k_bits), O.upcast(v_bits), O.upcast(q_bits)
+        worst = 0.0
+        for r, (f0, t) in enumerate(zip(first.tolist(), n_keys)):
+            ref = O.causal_attention(qf[r].reshape(1, hq, hd), kf[f0:f0 + t].reshape(t, hkv, hd), vf[f0:f0 + t].reshape(t, hkv, hd),
+                                     np.array([t - 1]))[0]
+            worst = max(worst, np.abs(got[r] - ref).max())
+            # fp32 scores and sums; the only roundings of size are the output's bf16 (2^-9 relative of |o| <~ 4)
+            np.testing.assert_allclose(got[r], ref, rtol=2 ** -8, atol=2e-3)
+        print("  max abs err", worst, flush=True)
+        with pytest.raises(P.VerilLMError) as e:
+            ctx.vl_op_attention_decode_bf16(d_q.data_ptr(), d_k.data_ptr(), d_v.data_ptr(), cache_rows, [cache_rows - 3], [4], d_o.data_ptr())
+        assert e.value.code == -1
+    finally:
+        ctx.close()
