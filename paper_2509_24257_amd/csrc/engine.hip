@@ -311,11 +311,9 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
     { StageSpan sp(c, VL_STAGE_QKV_GEMM); gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv); }
     {
         StageSpan sp(c, VL_STAGE_ROPE);
-        launch_rope(c->qkv, m.dtype, bi.pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
-        if (cache_row) {
-            const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
-            launch_kv_store(c->qkv, m.dtype, c->kcache + lo, c->vcache + lo, cache_row, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
-        }
+        const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
+        launch_rope(c->qkv, m.dtype, bi.pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s,
+                    cache_row ? c->kcache + lo : nullptr, cache_row ? c->vcache + lo : nullptr, cache_row);
         if (c->bf16) launch_transpose_v(c->qkv, c->vt, bi.vt_col, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, p.vt_ld, s);
     }
     {
@@ -343,8 +341,8 @@ void block_decode(vl_ctx* c, int l, int rows, const int32_t* pos, const int32_t*
     const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
     launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s);
     gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
-    launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
-    launch_kv_store(c->qkv, m.dtype, c->kcache + lo, c->vcache + lo, cache_row, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
+    launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s, c->kcache + lo, c->vcache + lo,
+                cache_row);
     if (c->bf16 && attn_decode_supported(m.n_q_heads, m.n_kv_heads, m.head_dim))
         launch_attn_decode(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, rows, m.n_q_heads,
                            m.n_kv_heads, m.head_dim, s);

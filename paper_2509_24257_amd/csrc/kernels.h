@@ -18,18 +18,16 @@ void launch_embed(const void* E, int dtype, const int32_t* tok, const int32_t* r
 void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int64_t rows, int d, float eps,
                     hipStream_t s);
 // Rotate query and key heads of qkv [rows][(hq+2hkv)*hd] in place using the cos/sin table
-// cs[pos][hd/2] (float2 = cos, sin).
+// cs[pos][hd/2] (float2 = cos, sin).  With cache_row != NULL the rotated keys and the values of row n are also
+// copied to row cache_row[n] of kcache / vcache ([cache rows][hkv*hd], same dtype).
 void launch_rope(void* qkv, int dtype, const int32_t* pos, const float2* cs, int64_t rows, int hq, int hkv,
-                 int hd, hipStream_t s);
+                 int hd, hipStream_t s, void* kcache = nullptr, void* vcache = nullptr, const int32_t* cache_row = nullptr);
 // vt[g][c][ vt_col[n] ] = V head g, channel c of token n (bf16); ldv = row pitch of vt in elements.
 void launch_transpose_v(const void* qkv, void* vt, const int32_t* vt_col, int64_t rows, int hq, int hkv, int hd,
                         int64_t ldv, hipStream_t s);
-// Copy K and V heads of qkv rows into the KV cache: cache row index = cache_row[n]; each cache row holds
-// hkv*hd elements.
-void launch_kv_store(const void* qkv, int dtype, void* kcache, void* vcache, const int32_t* cache_row,
-                     int64_t rows, int hq, int hkv, int hd, hipStream_t s);
-// out[(dst ? dst[n] : n), :] = resid[n, :] converted to `dtype`.
+// resid[n, :] = in[n, :] upcast exactly from `dtype` (the recorded states a segment starts from).
 void launch_load_hidden(const void* in, int dtype, float* resid, int64_t rows, int d, hipStream_t s);
+// out[(dst ? dst[n] : n), :] = resid[n, :] converted to `dtype`.
 void launch_store_hidden(const float* resid, void* out, int dtype, const int32_t* dst, int64_t rows, int d,
                          hipStream_t s);
 void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, int64_t rows, hipStream_t s);

@@ -9,7 +9,7 @@
 //             (l % LPK) * KPP + l / LPK of the block (LPK lanes per key, KPP keys per pass).
 //   softmax : online, per wave, in fp32 (running maximum and sum per query head).
 //   values  : per key one coalesced row read (lane l owns channels l*DPL .. +DPL-1); the key's probability is
-//             broadcast from the lane that holds it.
+//             broadcast from the lane that holds it.  Row reads are issued in batches ahead of their use.
 //   combine : the eight waves' (max, sum, weighted values) meet in LDS and are merged in wave order.
 #include "common.h"
 #include "kernels.h"
@@ -18,6 +18,20 @@ namespace vl {
 
 constexpr int AD_THREADS = 512;
 constexpr int AD_WAVES = 8;
+
+// DPL consecutive bf16 channels of one value row, held as loaded
+template <int DPL> struct VLoad;
+template <> struct VLoad<1> {
+    bf16 x;
+    __device__ __forceinline__ void load(const bf16* p) { x = *p; }
+    __device__ __forceinline__ float get(int) const { return (float)x; }
+};
+template <> struct VLoad<2> {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 x;
+    __device__ __forceinline__ void load(const bf16* p) { x = *(const bf16x2*)p; }
+    __device__ __forceinline__ float get(int i) const { return (float)x[i]; }
+};
 
 template <int G, int HD>
 __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __restrict__ q, int64_t q_stride,
@@ -28,6 +42,8 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
     constexpr int LPK = HD / 8;                                 // lanes per key row
     constexpr int KPP = WAVE / LPK;                             // keys per pass
     constexpr int DPL = HD / WAVE;                              // value channels per lane
+    constexpr int KCH = (G >= 4 && LPK > 8) ? 8 : LPK;          // key passes requested together
+    constexpr int VCH = G >= 8 ? 16 : 32;                       // value rows requested together
     __shared__ float part_o[AD_WAVES][G][HD];
     __shared__ float part_m[AD_WAVES][G], part_l[AD_WAVES][G];
     const int64_t row = blockIdx.x;
@@ -55,25 +71,40 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
     const int nblocks = (nkeys + WAVE - 1) / WAVE;
     for (int kb = wave; kb < nblocks; kb += AD_WAVES) {
         const int t0 = kb * WAVE;
-        // ---- scores: pass j covers keys t0 + j*KPP .. + KPP-1; rows past the last key re-read it and are masked below
+        // ---- loads go out in batches well ahead of their use (the step is latency-bound: few workgroups, short
+        // loops); the batch sizes keep the kernel inside the register file.  Rows past the last key re-read it and are
+        // masked below.  The first batch of value rows is requested before the scores are computed.
+        const bf16* vp = v + base * kv_stride + (int64_t)kvh * HD + lane * DPL;
+        VLoad<DPL> vr[VCH];
+#pragma unroll
+        for (int jj = 0; jj < VCH; ++jj) vr[jj].load(vp + (int64_t)min(t0 + jj, nkeys - 1) * kv_stride);
+        // ---- scores: pass j covers keys t0 + j*KPP .. + KPP-1
         float sc[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) sc[g] = -INFINITY;
-#pragma unroll 4
-        for (int j = 0; j < LPK; ++j) {
-            const int t = t0 + j * KPP + kin;
-            const bf16x8 kv = *(const bf16x8*)(k + (base + min(t, nkeys - 1)) * kv_stride + (int64_t)kvh * HD + sub * 8);
-            float kf[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) kf[i] = (float)kv[i];
+        for (int jc = 0; jc < LPK; jc += KCH) {
+            bf16x8 kreg[KCH];
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float d = 0.f;
+            for (int j = 0; j < KCH; ++j) {
+                const int t = t0 + (jc + j) * KPP + kin;
+                kreg[j] = *(const bf16x8*)(k + (base + min(t, nkeys - 1)) * kv_stride + (int64_t)kvh * HD + sub * 8);
+            }
 #pragma unroll
-                for (int i = 0; i < 8; ++i) d = fmaf(qr[g][i], kf[i], d);
+            for (int j = 0; j < KCH; ++j) {
+                const int t = t0 + (jc + j) * KPP + kin;
+                float kf[8];
 #pragma unroll
-                for (int s = LPK / 2; s > 0; s >>= 1) d += __shfl_xor(d, s, WAVE);
-                if (sub == j) sc[g] = (t < nkeys) ? d : -INFINITY;
+                for (int i = 0; i < 8; ++i) kf[i] = (float)kreg[j][i];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float d = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) d = fmaf(qr[g][i], kf[i], d);
+#pragma unroll
+                    for (int s = LPK / 2; s > 0; s >>= 1) d += __shfl_xor(d, s, WAVE);
+                    if (sub == jc + j) sc[g] = (t < nkeys) ? d : -INFINITY;
+                }
             }
         }
         // ---- online softmax; lane `lane` now holds key t0 + sub*KPP + kin
@@ -88,26 +119,28 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
 #pragma unroll
             for (int i = 0; i < DPL; ++i) o[g][i] *= corr;
         }
-        // ---- weighted values, keys in order
-        const int cnt = min(WAVE, nkeys - t0);
-        const bf16* vp = v + (base + t0) * kv_stride + (int64_t)kvh * HD + lane * DPL;
-#pragma unroll 4
-        for (int jj = 0; jj < cnt; ++jj) {
-            float vf[DPL];
-            if (DPL == 1) {
-                vf[0] = (float)vp[(int64_t)jj * kv_stride];
-            } else {
-                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-                const bf16x2 t = *(const bf16x2*)(vp + (int64_t)jj * kv_stride);
-                vf[0] = (float)t[0];
-                vf[DPL - 1] = (float)t[1];
-            }
-            const int src = (jj % KPP) * LPK + jj / KPP;        // the lane that holds key jj's probability
+        // ---- weighted values, keys in order; a masked key has probability 0
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[g]), src));
+        for (int c = 0; c < WAVE; c += VCH) {
+            if (t0 + c < nkeys) {                               // uniform
+                VLoad<DPL> vn[VCH];
+                if (c + VCH < WAVE && t0 + c + VCH < nkeys) {
 #pragma unroll
-                for (int i = 0; i < DPL; ++i) o[g][i] = fmaf(pj, vf[i], o[g][i]);
+                    for (int jj = 0; jj < VCH; ++jj) vn[jj].load(vp + (int64_t)min(t0 + c + VCH + jj, nkeys - 1) * kv_stride);
+                }
+#pragma unroll
+                for (int jj = 0; jj < VCH; ++jj) {
+                    const int key = c + jj;
+                    const int src = (key % KPP) * LPK + key / KPP;      // the lane that holds this key's probability
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float pj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(p[g]), src));
+#pragma unroll
+                        for (int i = 0; i < DPL; ++i) o[g][i] = fmaf(pj, vr[jj].get(i), o[g][i]);
+                    }
+                }
+#pragma unroll
+                for (int jj = 0; jj < VCH; ++jj) vr[jj] = vn[jj];
             }
         }
     }

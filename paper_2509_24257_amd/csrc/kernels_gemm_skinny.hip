@@ -1,7 +1,8 @@
 // C[M,N] = A[M,K] * W[N,K]^T for M <= 64 rows: the GEMM of the token-by-token path (Section 5.5), where a step
 // carries one row per live sequence and the whole cost is streaming W out of HBM once.
 //
-//   workgroup : 512 lanes = 8 waves; owns 32 rows of W (two groups of 16) and all M rows of A
+//   workgroup : 512 lanes = 8 waves; owns NG groups of 16 rows of W (two for wide matrices and for SwiGLU, one when N
+//               is small, so that the grid still covers the chip) and all M rows of A
 //   split K   : wave w reduces its own eighth of K, so that even N = 4096 puts 1024 waves and ~12 x 16 B per lane of
 //               loads in flight; the eight partial tiles meet in LDS and are summed in wave order (fixed, so the
 //               result is bit-reproducible)
@@ -20,10 +21,11 @@ namespace vl {
 constexpr int GS_THREADS = 512;
 constexpr int GS_WAVES = 8;
 
-template <int EPI, int MT>
+template <int EPI, int MT, int NG>
 __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                                                                  int M, int N, int K, void* __restrict__ outp) {
-    __shared__ __align__(16) float red[GS_WAVES][2 * MT * 256];
+    static_assert(EPI != EPI_SWIGLU || NG == 2, "SwiGLU pairs a gate group with an up group");
+    __shared__ __align__(16) float red[GS_WAVES][NG * MT * 256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int fr = lane & 15, fq = lane >> 4;
     int r0, r1, ch0 = 0;                                        // first W row of each group; first output channel (SwiGLU)
@@ -33,7 +35,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
         r1 = r0 + 32;
         ch0 = b * 32 + h * 16;
     } else {
-        r0 = blockIdx.x * 32;
+        r0 = blockIdx.x * (16 * NG);
         r1 = r0 + 16;
     }
     const bf16* w0 = W + (int64_t)min(r0 + fr, N - 1) * K + fq * 8;
@@ -42,9 +44,9 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
 #pragma unroll
     for (int t = 0; t < MT; ++t) ap[t] = A + (int64_t)min(t * 16 + fr, M - 1) * K + fq * 8;
 
-    f32x4 acc[2][MT];
+    f32x4 acc[NG][MT];
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[g][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
         for (int u = 0; u < 4; ++u) {
             const int o = (ks + u) * 32;
             a0[u] = *(const bf16x8*)(w0 + o);
-            a1[u] = *(const bf16x8*)(w1 + o);
+            if (NG == 2) a1[u] = *(const bf16x8*)(w1 + o);
 #pragma unroll
             for (int t = 0; t < MT; ++t) b[t][u] = *(const bf16x8*)(ap[t] + o);
         }
@@ -66,21 +68,21 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
                 acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[t][u], acc[0][t], 0, 0, 0);
-                acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[t][u], acc[1][t], 0, 0, 0);
+                if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[t][u], acc[NG - 1][t], 0, 0, 0);
             }
     }
     for (; ks < ke; ++ks) {
         const int o = ks * 32;
-        const bf16x8 a0 = *(const bf16x8*)(w0 + o), a1 = *(const bf16x8*)(w1 + o);
+        const bf16x8 a0 = *(const bf16x8*)(w0 + o), a1 = *(const bf16x8*)((NG == 2 ? w1 : w0) + o);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const bf16x8 b = *(const bf16x8*)(ap[t] + o);
             acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][t], 0, 0, 0);
-            acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[1][t], 0, 0, 0);
+            if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[NG - 1][t], 0, 0, 0);
         }
     }
 #pragma unroll
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int t = 0; t < MT; ++t) *(f32x4*)&red[wave][((g * MT + t) * 64 + lane) * 4] = acc[g][t];
     __syncthreads();
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
             if (m < M && f < F) ((bf16*)outp)[(int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
         }
     } else {
-        for (int e = threadIdx.x; e < 2 * PER_GROUP; e += GS_THREADS) {
+        for (int e = threadIdx.x; e < NG * PER_GROUP; e += GS_THREADS) {
             float v = 0.f;
 #pragma unroll
             for (int w = 0; w < GS_WAVES; ++w) v += red[w][e];
@@ -118,12 +120,19 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
     }
 }
 
-template <int EPI>
+template <int EPI, int NG>
 static void launch_mt(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s) {
-    const unsigned grid = (EPI == EPI_SWIGLU) ? (unsigned)(N / 32) : (unsigned)((N + 31) / 32);
-    if (M <= 16) gemm_skinny_kernel<EPI, 1><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
-    else if (M <= 32) gemm_skinny_kernel<EPI, 2><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
-    else gemm_skinny_kernel<EPI, 4><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
+    const unsigned grid = (unsigned)((N + 16 * NG - 1) / (16 * NG));
+    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
+    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
+    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
+}
+
+// one row group per workgroup while two would leave fewer than two workgroups per compute unit
+template <int EPI>
+static void launch_ng(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s) {
+    if (EPI == EPI_SWIGLU || N >= 32 * 512) launch_mt<EPI, 2>(A, W, M, N, K, out, s);
+    else launch_mt<EPI == EPI_SWIGLU ? EPI_STORE : EPI, 1>(A, W, M, N, K, out, s);
 }
 
 void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s) {
@@ -131,10 +140,10 @@ void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int e
     const bf16* a = (const bf16*)A;
     const bf16* w = (const bf16*)W;
     switch (epi) {
-        case EPI_STORE: launch_mt<EPI_STORE>(a, w, M, N, K, out, s); break;
-        case EPI_STORE_F32: launch_mt<EPI_STORE_F32>(a, w, M, N, K, out, s); break;
-        case EPI_ADD_RESID: launch_mt<EPI_ADD_RESID>(a, w, M, N, K, out, s); break;
-        default: launch_mt<EPI_SWIGLU>(a, w, M, N, K, out, s); break;
+        case EPI_STORE: launch_ng<EPI_STORE>(a, w, M, N, K, out, s); break;
+        case EPI_STORE_F32: launch_ng<EPI_STORE_F32>(a, w, M, N, K, out, s); break;
+        case EPI_ADD_RESID: launch_ng<EPI_ADD_RESID>(a, w, M, N, K, out, s); break;
+        default: launch_ng<EPI_SWIGLU>(a, w, M, N, K, out, s); break;
     }
 }
 

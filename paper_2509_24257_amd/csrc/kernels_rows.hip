@@ -85,32 +85,90 @@ void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int
 }
 
 // ---------------------------------------------------------------- rotary embedding, in place on Q and K
+// With cache_row != NULL the rotated keys and the values of row n are also written to row cache_row[n] of the KV
+// cache (kc, vc: [cache rows][hkv*hd]), which saves the token-by-token path a launch per layer.
 template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void rope_kernel(T* __restrict__ qkv, const int32_t* __restrict__ pos,
-                                                            const float2* __restrict__ cs, int hq, int hkv, int hd) {
+                                                            const float2* __restrict__ cs, int hq, int hkv, int hd,
+                                                            T* __restrict__ kc, T* __restrict__ vc,
+                                                            const int32_t* __restrict__ cache_row) {
     const int64_t n = blockIdx.x;
     const int half = hd >> 1;
     const int p = pos[n];
     T* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd;
     const float2* tab = cs + (int64_t)p * half;
     const int pairs = (hq + hkv) * half;           // query heads then key heads are contiguous in the row
+    const int64_t dst = cache_row ? (int64_t)cache_row[n] * hkv * hd : 0;
     for (int i = threadIdx.x; i < pairs; i += ROW_THREADS) {
         const int h = i / half, c = i - h * half;
         const float2 t = tab[c];
         T* a = row + h * hd + c;
         const float x1 = to_f32(a[0]), x2 = to_f32(a[half]);
-        a[0] = from_f32<T>(x1 * t.x - x2 * t.y);
-        a[half] = from_f32<T>(x2 * t.x + x1 * t.y);
+        const T y1 = from_f32<T>(x1 * t.x - x2 * t.y), y2 = from_f32<T>(x2 * t.x + x1 * t.y);
+        a[0] = y1;
+        a[half] = y2;
+        if (cache_row && h >= hq) {
+            T* kd = kc + dst + (h - hq) * hd + c;
+            kd[0] = y1;
+            kd[half] = y2;
+        }
+    }
+    if (cache_row) {
+        const T* vrow = row + (int64_t)(hq + hkv) * hd;
+        for (int i = threadIdx.x; i < hkv * hd; i += ROW_THREADS) vc[dst + i] = vrow[i];
+    }
+}
+
+// bf16 rows whose half head is a multiple of 8: the same rotation on 16-byte vectors (8 pairs per item)
+__global__ __launch_bounds__(ROW_THREADS) void rope_vec_kernel(bf16* __restrict__ qkv, const int32_t* __restrict__ pos,
+                                                                const float2* __restrict__ cs, int hq, int hkv, int hd,
+                                                                bf16* __restrict__ kc, bf16* __restrict__ vc,
+                                                                const int32_t* __restrict__ cache_row) {
+    const int64_t n = blockIdx.x;
+    const int half = hd >> 1, vph = half >> 3;     // vectors per half head
+    const int p = pos[n];
+    bf16* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd;
+    const float2* tab = cs + (int64_t)p * half;
+    const int items = (hq + hkv) * vph;
+    const int64_t dst = cache_row ? (int64_t)cache_row[n] * hkv * hd : 0;
+    for (int i = threadIdx.x; i < items; i += ROW_THREADS) {
+        const int h = i / vph, c = (i - h * vph) * 8;
+        bf16* a = row + h * hd + c;
+        const bf16x8 x1 = *(const bf16x8*)a, x2 = *(const bf16x8*)(a + half);
+        bf16x8 y1, y2;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float2 t = tab[c + j];
+            const float f1 = (float)x1[j], f2 = (float)x2[j];
+            y1[j] = (bf16)(f1 * t.x - f2 * t.y);
+            y2[j] = (bf16)(f2 * t.x + f1 * t.y);
+        }
+        *(bf16x8*)a = y1;
+        *(bf16x8*)(a + half) = y2;
+        if (cache_row && h >= hq) {
+            bf16* kd = kc + dst + (h - hq) * hd + c;
+            *(bf16x8*)kd = y1;
+            *(bf16x8*)(kd + half) = y2;
+        }
+    }
+    if (cache_row) {
+        const bf16* vrow = row + (int64_t)(hq + hkv) * hd;
+        for (int i = threadIdx.x * 8; i < hkv * hd; i += ROW_THREADS * 8) *(bf16x8*)(vc + dst + i) = *(const bf16x8*)(vrow + i);
     }
 }
 
 void launch_rope(void* qkv, int dtype, const int32_t* pos, const float2* cs, int64_t rows, int hq, int hkv, int hd,
-                 hipStream_t s) {
+                 hipStream_t s, void* kcache, void* vcache, const int32_t* cache_row) {
     if (rows <= 0) return;
-    if (dtype == VL_BF16)
-        rope_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((bf16*)qkv, pos, cs, hq, hkv, hd);
+    if (dtype == VL_BF16 && (hd & 15) == 0)
+        rope_vec_kernel<<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((bf16*)qkv, pos, cs, hq, hkv, hd, (bf16*)kcache, (bf16*)vcache,
+                                                                     cache_row);
+    else if (dtype == VL_BF16)
+        rope_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((bf16*)qkv, pos, cs, hq, hkv, hd, (bf16*)kcache,
+                                                                      (bf16*)vcache, cache_row);
     else
-        rope_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((float*)qkv, pos, cs, hq, hkv, hd);
+        rope_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((float*)qkv, pos, cs, hq, hkv, hd, (float*)kcache,
+                                                                       (float*)vcache, cache_row);
 }
 
 // ---------------------------------------------------------------- V transpose for the matrix-core attention
@@ -144,32 +202,6 @@ void launch_transpose_v(const void* qkv, void* vt, const int32_t* vt_col, int64_
     if (rows <= 0) return;
     dim3 grid((unsigned)((rows + 63) / 64), (unsigned)(hkv * hd / 64));
     transpose_v_kernel<<<grid, 256, 0, s>>>((const bf16*)qkv, (bf16*)vt, vt_col, rows, hq, hkv, hd, ldv);
-}
-
-// ---------------------------------------------------------------- KV-cache store
-template <typename T>
-__global__ __launch_bounds__(ROW_THREADS) void kv_store_kernel(const T* __restrict__ qkv, T* __restrict__ kc,
-                                                                T* __restrict__ vc, const int32_t* __restrict__ cache_row,
-                                                                int hq, int hkv, int hd) {
-    const int64_t n = blockIdx.x;
-    const int w = hkv * hd;
-    const T* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd + (int64_t)hq * hd;
-    const int64_t dst = (int64_t)cache_row[n] * w;
-    for (int i = threadIdx.x; i < w; i += ROW_THREADS) {
-        kc[dst + i] = row[i];
-        vc[dst + i] = row[w + i];
-    }
-}
-
-void launch_kv_store(const void* qkv, int dtype, void* kcache, void* vcache, const int32_t* cache_row, int64_t rows,
-                     int hq, int hkv, int hd, hipStream_t s) {
-    if (rows <= 0) return;
-    if (dtype == VL_BF16)
-        kv_store_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const bf16*)qkv, (bf16*)kcache, (bf16*)vcache,
-                                                                          cache_row, hq, hkv, hd);
-    else
-        kv_store_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const float*)qkv, (float*)kcache,
-                                                                           (float*)vcache, cache_row, hq, hkv, hd);
 }
 
 // ---------------------------------------------------------------- hidden-state store (commitments out)
