@@ -36,6 +36,31 @@ def attention_flops(model, lengths):
     return 4.0 * model.n_q_heads * model.head_dim * tri * model.n_layers
 
 
+# Bytes moved between L2 and the memory side by ONE launch of the gate/up GEMM at the default workload, from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads for a plain
+# 1 GiB -> 1 GiB elementwise kernel (0.500 and 1.000 on MI355X); the commands and raw figures are in profiles/.  The
+# figure belongs to one version of the kernel source: any edit of that file makes it unknown again.
+GATEUP_TRAFFIC = {
+    "source": "paper_2509_24257_amd/csrc/kernels_gemm_mfma.hip",
+    "sha256": "348e4dbcecfa3b78a7e42f8023fe49c7a3ecfa8652a9885fd8c138d24949724f",
+    "workload": "cfg1-8b-b8x1024",
+    "bytes_per_launch": (1377287 / 0.500 + 229376 / 1.000) * 1024,
+}
+
+
+def measured_traffic(wl):
+    import hashlib
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), GATEUP_TRAFFIC["source"])
+    try:
+        with open(path, "rb") as f:
+            same = hashlib.sha256(f.read()).hexdigest() == GATEUP_TRAFFIC["sha256"]
+    except OSError:
+        same = False
+    if not same or wl.name != GATEUP_TRAFFIC["workload"]:
+        return None
+    return round(GATEUP_TRAFFIC["bytes_per_launch"])
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -189,7 +214,7 @@ def main():
         "flags_match_tamper_mask": flags_ok,
         "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel<SWIGLU> (gate/up GEMM, M=%d N=%d K=%d)" % (n, 2 * m.d_ffn, m.d_model),
                      "achieved": round(gu_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gu_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(gu_tflops / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(wl),
                      "avg_launch_ms": round(gu_avg_ms, 4), "launches": gu_launches},
         "stages_ms": stages,
         "compare_stage": {"achieved_GBps": round(compare_gbs, 1) if compare_gbs else None,
