@@ -30,6 +30,9 @@ following norm, for every l including the last.
 * Section 7 "Bit-aware statistical comparison" (P_e, P_m, P_w, mean discrepancy and their calibrated
   thresholds) and the offline test battery of Appendix A.1 (P_exp, Q_small, Z_large, MAE)
                                                                                 -> `bit_compare`, `bit_rule`.
+* Section 5.6 "Commitment Submission" / Section 5.7 MerkleVerify: a SHA-256 Merkle tree over the canonical
+  float32 scalars of a state, its root, inclusion proofs and their check    -> `merkle_root`, `merkle_open`,
+  `merkle_verify`.
 
 Readings that go beyond the paper (per-token relative L2 and max-abs instead of one verdict per
 segment; a logit margin for near-tied argmax) are documented where they are implemented.
@@ -402,6 +405,80 @@ def bit_rule(counts: dict, mean_signed: np.ndarray, pe_max: float, pm_min: float
         ok &= counts["n_small"].astype(np.float32) >= f(q_small_min) * d
         ok &= counts["n_large"].astype(np.float32) <= f(z_large_max) * d
     return ok
+
+
+
+# ----------------------------------------------------------------------------------------------
+# Merkle commitment of a hidden state (Section 5.6 "Commitment Submission": root = MerkleRoot(S) over a
+# canonical serialization with scalar elements as leaves; Section 7: canonical float32, SHA-256)
+# ----------------------------------------------------------------------------------------------
+import hashlib
+
+
+def _sha256(b: bytes) -> bytes:
+    return hashlib.sha256(b).digest()
+
+
+def merkle_leaves(state_row: np.ndarray) -> List[bytes]:
+    """Leaf digests of one token's state: element j -> SHA-256 of its 4 little-endian float32 bytes.
+
+    The state is taken in canonical float32 (a bf16 record is upcast exactly; a wider recomputation is rounded).
+    """
+    a = np.asarray(state_row)
+    a = upcast(a).astype(np.float32) if a.dtype == np.uint16 else a.astype(np.float32)
+    raw = a.astype("<f4").tobytes()
+    return [_sha256(raw[4 * j:4 * j + 4]) for j in range(a.shape[-1])]
+
+
+def merkle_levels(leaves: List[bytes]) -> List[List[bytes]]:
+    """All levels of the tree, leaves first.  An inner node is SHA-256(left || right); a node without a right
+    neighbour at its level moves up unchanged.  (The paper fixes neither rule; this is the plainest reading.)"""
+    levels = [list(leaves)]
+    while len(levels[-1]) > 1:
+        cur = levels[-1]
+        nxt = [_sha256(cur[i] + cur[i + 1]) for i in range(0, len(cur) - 1, 2)]
+        if len(cur) % 2:
+            nxt.append(cur[-1])
+        levels.append(nxt)
+    return levels
+
+
+def merkle_root(state_row: np.ndarray) -> bytes:
+    return merkle_levels(merkle_leaves(state_row))[-1][0]
+
+
+def merkle_roots(states: np.ndarray) -> np.ndarray:
+    """Roots of every row of states [R, d] -> uint8 [R, 32]."""
+    return np.stack([np.frombuffer(merkle_root(r), dtype=np.uint8) for r in states])
+
+
+def merkle_open(state_row: np.ndarray, index: int) -> List[bytes]:
+    """Inclusion proof of element `index`: the sibling digests from the leaf level upwards; a level at which the
+    node has no sibling (it moves up unchanged) contributes nothing."""
+    levels = merkle_levels(merkle_leaves(state_row))
+    path, i = [], int(index)
+    for cur in levels[:-1]:
+        sib = i ^ 1
+        if sib < len(cur):
+            path.append(cur[sib])
+        i >>= 1
+    return path
+
+
+def merkle_verify(root: bytes, value: float, index: int, n_leaves: int, path: Sequence[bytes]) -> bool:
+    """MerkleVerify of Section 5.7: recompute the root from the disclosed scalar, its index and the proof."""
+    h = _sha256(np.asarray(value, dtype="<f4").tobytes())
+    i, n, k = int(index), int(n_leaves), 0
+    while n > 1:
+        sib = i ^ 1
+        if sib < n:
+            if k >= len(path):
+                return False
+            h = _sha256(h + path[k]) if i % 2 == 0 else _sha256(path[k] + h)
+            k += 1
+        i >>= 1
+        n = (n + 1) // 2
+    return k == len(path) and h == root
 
 
 def token_check(logits: np.ndarray, committed_argmax: np.ndarray, margin: float):
