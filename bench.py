@@ -131,6 +131,20 @@ def main():
     t_commit = time.perf_counter() - t0
     log(f"[bench] commitments by {'prefill' if args.no_decode else 'prefill(prompt)+token-by-token decode'}: {t_commit:.2f} s")
 
+    # ---- the commitment step that follows in the protocol: Merkle roots over the committed states (not part of `value`)
+    merkle = None
+    if c:
+        d_roots = torch.zeros((c * n, 32), dtype=torch.uint8, device=dev)
+        ctx.vl_op_merkle_roots(d_com.data_ptr(), hd_code, c * n, d_roots.data_ptr())          # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.vl_op_merkle_roots(d_com.data_ptr(), hd_code, c * n, d_roots.data_ptr())
+        torch.cuda.synchronize()
+        t_mk = time.perf_counter() - t0
+        merkle = {"roots": c * n, "scalars_per_root": m.d_model, "ms": round(t_mk * 1e3, 3),
+                  "ns_per_scalar": round(t_mk / (c * n * m.d_model) * 1e9, 4)}
+        log(f"[bench] Merkle roots of the {c} x {n} committed states: {t_mk * 1e3:.1f} ms")
+
     # ---- tamper (host side, from the seeded generator), back to HBM
     pos = synth.tamper_positions(wl)
     if bf:
@@ -222,6 +236,7 @@ def main():
         "commit_seconds": round(t_commit, 3),
         "verify_over_commit_cost": round((ms_per_step * 1e-3) / t_commit, 5),
         "commit_kind": "prefill" if args.no_decode else "prefill(prompt)+decode",
+        "merkle_commit": merkle,
     }
 
     # ---- CPU baseline: the oracle, untuned, on a bounded sample of the same workload

@@ -304,6 +304,28 @@ int vl_op_compare(vl_ctx* ctx, const float* h_hat, const void* committed, int32_
 int vl_op_argmax(vl_ctx* ctx, const float* logits, int64_t N, const int32_t* committed_argmax, float margin,
                  int32_t* out_argmax, float* out_gap, uint8_t* out_ok);
 
+/* ---- Merkle commitment of hidden states (Section 5.6 "Commitment Submission", Section 5.7 MerkleVerify) ---------
+ * A state row (d_model scalars) is serialised as canonical float32 (a bf16 row is upcast exactly), little endian.
+ * Leaf j = SHA-256 of the 4 bytes of element j; inner node = SHA-256(left || right); a node without a right
+ * neighbour at its level moves up unchanged; the root is the last node left.  Digests are 32 bytes, in the order
+ * SHA-256 defines them. */
+#define VL_MERKLE_DIGEST_BYTES 32
+#define VL_MERKLE_MAX_OPENINGS 64
+
+/* roots [device] out uint8 [rows][32]: the root of every row of states [device] [rows][d_model] in `dtype`.
+   Any number of rows (for the states of C committed layers pass rows = C * N).  d_model <= 16384. */
+int vl_op_merkle_roots(vl_ctx* ctx, const void* states, int32_t dtype, int64_t rows, uint8_t* roots);
+
+/* Inclusion proofs for K <= VL_MERKLE_MAX_OPENINGS disclosed scalars: opening q is element sel_index[q] of row
+   sel_row[q] (both [host]) of states [device] [rows][d_model].
+   values   [device] out float32 [K], the disclosed scalars, or NULL
+   paths    [device] out uint8 [K][depth][32] with depth = ceil(log2 d_model): the sibling digests from the leaf level
+            upwards; a level where the node has no sibling contributes nothing, and entries past the proof are zero
+   path_len [host]   out int32 [K], the number of digests of each proof, or NULL
+   The receiver recomputes the root from (value, index, d_model, path). */
+int vl_op_merkle_open(vl_ctx* ctx, const void* states, int32_t dtype, int64_t rows, const int64_t* sel_row,
+                      const int32_t* sel_index, int32_t K, float* values, uint8_t* paths, int32_t* path_len);
+
 /* vl_op_compare plus the bit-aware rule on the same rows: h_hat [device] float32 [N][d_model], committed [device]
    [N][d_model] in hidden_dtype; stats [device] out vl_tok_stats [N] or NULL, bits [device] out vl_bit_stats [N] or
    NULL, ok [device] out uint8 [N] (tolerance test AND rule) or NULL. */

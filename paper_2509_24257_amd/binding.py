@@ -17,7 +17,8 @@ _STATUS = {0: "VL_OK", -1: "VL_E_ARG", -2: "VL_E_WEIGHTS", -3: "VL_E_CAPACITY", 
 EXPORTS = ["vl_plan_memory", "vl_create", "vl_load_weights", "vl_destroy", "vl_last_error", "vl_verify_prefill",
            "vl_verify_segment", "vl_prefill_commit", "vl_decode_commit", "vl_get_logits", "vl_get_argmax",
            "vl_set_bit_rule", "vl_get_bit_stats", "vl_profile_enable", "vl_profile_read", "vl_op_gemm_bf16",
-           "vl_op_attention_bf16", "vl_op_attention_decode_bf16", "vl_op_compare", "vl_op_compare_bits", "vl_op_argmax"]
+           "vl_op_attention_bf16", "vl_op_attention_decode_bf16", "vl_op_compare", "vl_op_compare_bits", "vl_op_argmax", "vl_op_merkle_roots",
+           "vl_op_merkle_open"]
 
 
 STAGES = ["embed", "norm", "qkv_gemm", "rope", "attention", "o_gemm", "gateup_gemm", "down_gemm", "compare", "lm_gemm",
@@ -108,6 +109,8 @@ def load_library():
     lib.vl_op_attention_bf16.argtypes = [vp, vp, i32p, C.c_int32, vp]
     lib.vl_op_attention_decode_bf16.argtypes = [vp, vp, vp, vp, C.c_int64, i32p, i32p, C.c_int32, vp]
     lib.vl_op_compare.argtypes = [vp, vp, vp, C.c_int32, C.c_int64, C.POINTER(Tol), vp, vp]
+    lib.vl_op_merkle_roots.argtypes = [vp, vp, C.c_int32, C.c_int64, vp]
+    lib.vl_op_merkle_open.argtypes = [vp, vp, C.c_int32, C.c_int64, C.POINTER(C.c_int64), i32p, C.c_int32, vp, vp, i32p]
     lib.vl_op_argmax.argtypes = [vp, vp, C.c_int64, vp, C.c_float, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("vl_destroy", "vl_last_error"):
@@ -244,6 +247,20 @@ class Context:
         self._check(lib().vl_op_attention_decode_bf16(self._h, C.c_void_p(q or None), C.c_void_p(k_cache or None),
                                                       C.c_void_p(v_cache or None), int(cache_rows), fa, na, rows,
                                                       C.c_void_p(out or None)))
+
+    def vl_op_merkle_roots(self, states: int, dtype: int, rows: int, roots: int):
+        self._check(lib().vl_op_merkle_roots(self._h, C.c_void_p(states or None), int(dtype), int(rows), C.c_void_p(roots or None)))
+
+    def vl_op_merkle_open(self, states: int, dtype: int, rows: int, sel_row: Sequence[int], sel_index: Sequence[int], values: int,
+                          paths: int):
+        """Returns the list of proof lengths."""
+        k = len(sel_row)
+        ra = (C.c_int64 * max(k, 1))(*[int(v) for v in sel_row])
+        ia, _ = _i32(sel_index)
+        lens = (C.c_int32 * max(k, 1))()
+        self._check(lib().vl_op_merkle_open(self._h, C.c_void_p(states or None), int(dtype), int(rows), ra, ia, k,
+                                            C.c_void_p(values or None), C.c_void_p(paths or None), lens))
+        return [int(v) for v in lens[:k]]
 
     def vl_op_compare(self, h_hat: int, committed: int, hidden_dtype: int, n: int, tol: Tol, stats: int, ok: int):
         self._check(lib().vl_op_compare(self._h, C.c_void_p(h_hat or None), C.c_void_p(committed or None), int(hidden_dtype),

@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libverillm.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["engine.hip", "kernels_rows.hip", "kernels_gemm_simple.hip", "kernels_gemm_mfma.hip", "kernels_gemm_skinny.hip", "kernels_attn_decode.hip",
-           "kernels_attn_rowwise.hip", "kernels_attn_mfma.hip", "kernels_compare.hip"]
+           "kernels_attn_rowwise.hip", "kernels_attn_mfma.hip", "kernels_compare.hip", "kernels_merkle.hip"]
 
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          # packed-fp32 instructions are kept out of every kernel (the compiler otherwise forms them at -O3)

@@ -98,6 +98,7 @@ Plan make_plan(const vl_model_cfg& c) {
     w += align_up(p.stage_ints * 4, ALIGN);              // per-call index arrays
     w += align_up((int64_t)p.L * p.N * (int64_t)sizeof(vl_tok_stats), ALIGN);
     w += align_up((int64_t)p.L * p.N * (int64_t)sizeof(vl_bit_stats), ALIGN);
+    w += align_up((int64_t)VL_MERKLE_MAX_OPENINGS * 2 * p.d * 32, ALIGN);
     w += 3 * align_up(p.N, ALIGN) + align_up(p.N * 4, ALIGN) * 2 + ALIGN;   // ok bytes, argmax, gap, summary
     p.workspace_total = w;
     return p;
@@ -136,6 +137,7 @@ struct vl_ctx {
     int32_t* h_idx = nullptr;           // pinned host staging for them
     vl_tok_stats* stats = nullptr;
     vl_bit_stats* bit_stats = nullptr;  // [L][N], written only while a bit rule is set
+    uint32_t* merkle_scratch = nullptr; // VL_MERKLE_MAX_OPENINGS x 2 x d_model digests, for inclusion proofs
     bool has_rule = false;
     vl_bit_rule rule{};
     int last_bits_c = 0;                // committed layers of the most recent verify call that ran the rule
@@ -603,6 +605,7 @@ int vl_create(const vl_model_cfg* cfg, int device, void* hip_stream, vl_ctx** ou
     if ((rc = dev_alloc(c, &c->d_idx, p.stage_ints * 4, true))) return bail(rc);
     if ((rc = dev_alloc(c, &c->stats, p.L * p.N * (int64_t)sizeof(vl_tok_stats), false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->bit_stats, p.L * p.N * (int64_t)sizeof(vl_bit_stats), false))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->merkle_scratch, (int64_t)VL_MERKLE_MAX_OPENINGS * 2 * p.d * 32, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->hid_ok, p.N, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->tok_ok, p.N, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->scratch_ok, p.N, false))) return bail(rc);
@@ -987,6 +990,58 @@ int vl_op_compare_bits(vl_ctx* c, const float* h_hat, const void* committed, int
     if (N == 0) return VL_OK;
     HIP_TRY(c, hipSetDevice(c->device));
     launch_compare(h_hat, committed, hidden_dtype, N, c->cfg.d_model, tol->rel_l2, tol->max_abs, stats, nullptr, ok, c->stream, rule, bits);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return VL_OK;
+}
+
+int vl_op_merkle_roots(vl_ctx* c, const void* states, int32_t dtype, int64_t rows, uint8_t* roots) {
+    if (!c) return VL_E_ARG;
+    if (rows < 0 || (rows > 0 && (!states || !roots))) return c->fail(VL_E_ARG, "bad pointer or rows < 0");
+    if (dtype != VL_F32 && dtype != VL_BF16) return c->fail(VL_E_ARG, "dtype must be VL_F32 or VL_BF16");
+    if (c->cfg.d_model > 16384) return c->fail(VL_E_CAPACITY, "Merkle trees are built for d_model <= 16384");
+    if (rows > 0x7fffffff) return c->fail(VL_E_CAPACITY, "more than 2^31 - 1 rows in one call");
+    if (rows == 0) return VL_OK;
+    HIP_TRY(c, hipSetDevice(c->device));
+    launch_merkle_roots(states, dtype, rows, c->cfg.d_model, roots, c->stream);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return VL_OK;
+}
+
+int vl_op_merkle_open(vl_ctx* c, const void* states, int32_t dtype, int64_t rows, const int64_t* sel_row, const int32_t* sel_index,
+                      int32_t K, float* values, uint8_t* paths, int32_t* path_len) {
+    if (!c) return VL_E_ARG;
+    if (K < 0 || (K > 0 && (!states || !sel_row || !sel_index || !paths))) return c->fail(VL_E_ARG, "bad pointer or K < 0");
+    if (dtype != VL_F32 && dtype != VL_BF16) return c->fail(VL_E_ARG, "dtype must be VL_F32 or VL_BF16");
+    if (K > VL_MERKLE_MAX_OPENINGS) return c->fail(VL_E_CAPACITY, fmt("K = %d exceeds VL_MERKLE_MAX_OPENINGS = %d", K, VL_MERKLE_MAX_OPENINGS));
+    const int d = c->cfg.d_model;
+    if (d > 16384) return c->fail(VL_E_CAPACITY, "Merkle trees are built for d_model <= 16384");
+    for (int q = 0; q < K; ++q)
+        if (sel_row[q] < 0 || sel_row[q] >= rows || sel_row[q] > 0x7fffffff || sel_index[q] < 0 || sel_index[q] >= d)
+            return c->fail(VL_E_ARG, fmt("opening %d: row %lld / element %d outside [0, %lld) x [0, %d)", q, (long long)sel_row[q],
+                                         sel_index[q], (long long)rows, d));
+    if (K == 0) return VL_OK;
+    HIP_TRY(c, hipSetDevice(c->device));
+    Stage st(c->h_idx, c->d_idx, c->plan.stage_ints);
+    int32_t *hr, *dr, *hi, *di;
+    if (!st.take(K, &hr, &dr) || !st.take(K, &hi, &di)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    for (int q = 0; q < K; ++q) {
+        hr[q] = (int32_t)sel_row[q];
+        hi[q] = sel_index[q];
+        if (path_len) {                                         // a level adds a digest iff the node has a sibling there
+            int n = d, idx = sel_index[q], len = 0;
+            while (n > 1) {
+                if ((idx ^ 1) < n) ++len;
+                idx >>= 1;
+                n = (n + 1) >> 1;
+            }
+            path_len[q] = len;
+        }
+    }
+    int rc = upload_stage(c, st);
+    if (rc) return rc;
+    launch_merkle_open(states, dtype, d, dr, di, K, c->merkle_scratch, paths, values, c->stream);
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return VL_OK;

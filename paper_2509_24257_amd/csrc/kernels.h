@@ -84,6 +84,17 @@ void launch_compare(const float* h_hat, const void* committed, int hidden_dtype,
                     const vl_bit_rule* rule = nullptr, vl_bit_stats* bit_stats = nullptr);
 void launch_argmax(const float* logits, int64_t rows, int vocab, const int32_t* committed, float margin,
                    int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s);
+// ---- Merkle commitment (kernels_merkle.hip) -----------------------------------------------------------
+// roots[r][32] = SHA-256 Merkle root over the d canonical-float32 scalars of states row r (dtype VL_F32 / VL_BF16);
+// d <= 16384.
+void launch_merkle_roots(const void* states, int dtype, int64_t rows, int d, uint8_t* roots, hipStream_t s);
+// ceil(log2 d): the longest inclusion proof
+int merkle_depth(int d);
+// Opening q discloses element sel_idx[q] of row sel_row[q]: values[q] (may be NULL) and the sibling digests, leaf level
+// first, in paths[q][depth][32] (entries past the proof's length are zero).  scratch: count * 2 * d * 32 bytes.
+void launch_merkle_open(const void* states, int dtype, int d, const int32_t* sel_row, const int32_t* sel_idx, int count,
+                        uint32_t* scratch, uint8_t* paths, float* values, hipStream_t s);
+
 struct DevSummary { unsigned long long n_rejected, n_hidden_reject, n_token_reject; float max_rel, max_abs, mean_mae; };
 void launch_finalize(const uint8_t* hid_ok, const uint8_t* tok_ok, const vl_tok_stats* stats, int C, int64_t rows,
                      uint8_t* flags, DevSummary* out, hipStream_t s);

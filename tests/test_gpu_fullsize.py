@@ -209,6 +209,31 @@ def test_workload1_decode_commitments_verify_clean(ctx_8b):
     print(f"  rel-L2 statistic vs oracle: exact-arithmetic model {d_exact:.2e}, bf16-operand model {d_fmt:.2e}", flush=True)
     assert d_exact <= 1.25e-2 * math.sqrt(8) and d_fmt <= 0.75e-2 * math.sqrt(8)
 
+    say("workload 1: Merkle roots of all 4 x 8192 committed states; sampled rows and openings against the oracle")
+    c_n = len(wl.commit_layers) * wl.n_tokens
+    d_st = H.to_dev(st_t.reshape(c_n, wl.model.d_model))
+    d_roots = torch.zeros((c_n, 32), dtype=torch.uint8, device=H.DEV)
+    t0 = time.time()
+    ctx_8b.vl_op_merkle_roots(d_st.data_ptr(), P.VL_BF16, c_n, d_roots.data_ptr())
+    dt = time.time() - t0
+    roots = d_roots.cpu().numpy()
+    print(f"  {c_n} roots over {wl.model.d_model} scalars each in {dt * 1e3:.1f} ms = {dt / (c_n * wl.model.d_model) * 1e9:.3f} ns per scalar", flush=True)
+    flat = st_t.reshape(c_n, wl.model.d_model)
+    sample = np.random.default_rng(7).choice(c_n, 10, replace=False)
+    for r in sample:
+        assert bytes(roots[r]) == O.merkle_root(flat[r])
+    assert len({bytes(r) for r in roots}) == c_n                       # all states differ, so do their roots
+    sel_row, sel_idx = [int(sample[0]), int(sample[1]), c_n - 1], [0, 2049, wl.model.d_model - 1]
+    d_paths = torch.zeros((3, 12, 32), dtype=torch.uint8, device=H.DEV)
+    d_vals = torch.zeros(3, dtype=torch.float32, device=H.DEV)
+    lens = ctx_8b.vl_op_merkle_open(d_st.data_ptr(), P.VL_BF16, c_n, sel_row, sel_idx, d_vals.data_ptr(), d_paths.data_ptr())
+    paths, vals = d_paths.cpu().numpy(), d_vals.cpu().numpy()
+    for q in range(3):
+        assert lens[q] == 12
+        proof = [bytes(paths[q, k]) for k in range(12)]
+        assert O.merkle_verify(bytes(roots[sel_row[q]]), vals[q], sel_idx[q], wl.model.d_model, proof)
+        assert not O.merkle_verify(bytes(roots[sel_row[q] - 1]), vals[q], sel_idx[q], wl.model.d_model, proof)
+
 
 def test_workload2_8b_varlen64(ctx_8b):
     wl = synth.workload(2)

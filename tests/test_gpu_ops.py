@@ -301,3 +301,49 @@ def test_decode_attention_matches_oracle(hq, hkv, hd):
         assert e.value.code == -1
     finally:
         ctx.close()
+
+
+# ------------------------------------------------------------------ Merkle commitment (Section 5.6 / 5.7)
+@pytest.mark.parametrize("d,dtype", [(256, "f32"), (256, "bf16"), (64, "f32"), (200, "bf16"), (4096, "bf16"), (8192, "f32"),
+                                     (1000, "f32"), (16384, "bf16"), (264, "f32"), (72, "bf16"), (8200, "f32"), (8, "f32")])
+def test_merkle_roots_and_openings_match_oracle(d, dtype):
+    say(f"merkle d={d} dtype={dtype}")
+    # the context only fixes d_model here (an fp32 model allows any multiple of 8); the state dtype is an argument
+    m = synth.small_model("f32", n_layers=1, d_model=d, n_q_heads=1, n_kv_heads=1, head_dim=64, d_ffn=64)
+    ctx = P.Context(H.c_cfg(m, 64, 4, 64), 0, 0)          # op calls need no weights
+    try:
+        rng = np.random.default_rng(d)
+        rows = 5 if d >= 4096 else 19
+        x = (rng.standard_normal((rows, d)) * 3).astype(np.float32)
+        x[0, 0], x[0, 1], x[1, d - 1] = 0.0, -0.0, np.inf
+        st = H.stored(x, dtype)
+        d_s = H.to_dev(st)
+        d_roots = torch.zeros((rows, 32), dtype=torch.uint8, device=H.DEV)
+        ctx.vl_op_merkle_roots(d_s.data_ptr(), H.hidden_dtype_code(dtype), rows, d_roots.data_ptr())
+        got = d_roots.cpu().numpy()
+        ref = O.merkle_roots(st)
+        np.testing.assert_array_equal(got, ref)                                    # bytes: bit-exact
+        # openings: first, last, a middle element and the ragged edge
+        sel_row = [0, rows - 1, rows // 2, 1, 2]
+        sel_idx = [0, d - 1, d // 2, d - 2 if d > 1 else 0, (d // 3) | 1 if d > 3 else 0]
+        depth = max(d - 1, 0).bit_length()
+        d_paths = torch.full((len(sel_row), depth, 32), 7, dtype=torch.uint8, device=H.DEV)
+        d_vals = torch.zeros(len(sel_row), dtype=torch.float32, device=H.DEV)
+        lens = ctx.vl_op_merkle_open(d_s.data_ptr(), H.hidden_dtype_code(dtype), rows, sel_row, sel_idx, d_vals.data_ptr(), d_paths.data_ptr())
+        paths, vals = d_paths.cpu().numpy(), d_vals.cpu().numpy()
+        vals_ref = O.upcast(st).astype(np.float32)
+        for q, (r, j) in enumerate(zip(sel_row, sel_idx)):
+            want = O.merkle_open(st[r], j)
+            assert lens[q] == len(want)
+            assert [bytes(paths[q, k]) for k in range(lens[q])] == want
+            assert not paths[q, lens[q]:].any()
+            assert vals[q].tobytes() == vals_ref[r, j].tobytes()
+            assert O.merkle_verify(bytes(got[r]), vals[q], j, d, [bytes(paths[q, k]) for k in range(lens[q])])
+        with pytest.raises(P.VerilLMError) as e:
+            ctx.vl_op_merkle_open(d_s.data_ptr(), H.hidden_dtype_code(dtype), rows, [rows], [0], 0, d_paths.data_ptr())
+        assert e.value.code == -1
+        with pytest.raises(P.VerilLMError) as e:
+            ctx.vl_op_merkle_open(d_s.data_ptr(), H.hidden_dtype_code(dtype), rows, [0] * 65, [0] * 65, 0, d_paths.data_ptr())
+        assert e.value.code == -3
+    finally:
+        ctx.close()
