@@ -14,6 +14,15 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int WAVE = 64;
 
+// Tiled image of a K-contiguous bf16 matrix [rows][K] (K a multiple of 32; rows padded to a multiple of 256): blocks of
+// 256 rows, and inside a block one contiguous 16 KB piece per k-tile of 32 (256 rows x 64 bytes).  This is exactly
+// what one k-step of a 256-row GEMM tile loads, so every such load covers whole 128-byte lines.  The operands of the
+// bf16 GEMMs (weights, normalised rows, attention output, SwiGLU output) live in this layout.
+constexpr int TL_ROWS = 256, TL_K = 32, TL_PIECE = TL_ROWS * TL_K;
+__host__ __device__ __forceinline__ int64_t tiled_off(int64_t row, int64_t k, int64_t K) {
+    return ((row >> 8) * (K >> 5) + (k >> 5)) * TL_PIECE + (row & 255) * TL_K + (k & 31);
+}
+
 // Storage-type conversions.  float -> bf16 is the hardware convert (round to nearest, ties to even).
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }

@@ -11,6 +11,7 @@
 #include <string>
 #include <vector>
 
+#include "common.h"
 #include "kernels.h"
 
 using namespace vl;
@@ -60,6 +61,8 @@ struct Plan {
     int64_t embed_bytes, lm_bytes, weights_total;
     int64_t vt_ld, max_tiles, stage_ints;
     int64_t workspace_total;
+    // bf16 models keep every GEMM operand as a tiled image (see tiled_off): row counts padded to whole 256-row blocks
+    int64_t Np, qkv_wp, dp, gup, Vp, wstage_bytes;
 };
 
 Plan make_plan(const vl_model_cfg& c) {
@@ -69,16 +72,20 @@ Plan make_plan(const vl_model_cfg& c) {
     p.qkv_w = p.qd + 2 * p.kvd; p.F = c.d_ffn; p.V = c.vocab; p.L = c.n_layers;
     p.N = c.max_tokens; p.B = c.max_seqs; p.T = c.max_seq_len;
     p.ib = c.dtype == VL_BF16 ? 32 : 16;
+    const bool tiled = c.dtype == VL_BF16;
+    auto pr = [&](int64_t rows) { return tiled ? align_up(rows, TL_ROWS) : rows; };
+    p.Np = pr(p.N); p.qkv_wp = pr(p.qkv_w); p.dp = pr(p.d); p.gup = pr(2 * p.F); p.Vp = pr(p.V);
+    p.wstage_bytes = tiled ? (int64_t)64 << 20 : 0;
     int64_t o = 0;
     p.off_attn_norm = o; o = align_up(o + p.d * 4, ALIGN);
-    p.off_wqkv = o; o = align_up(o + p.qkv_w * p.d * p.esz, ALIGN);
-    p.off_wo = o; o = align_up(o + p.d * p.qd * p.esz, ALIGN);
+    p.off_wqkv = o; o = align_up(o + p.qkv_wp * p.d * p.esz, ALIGN);
+    p.off_wo = o; o = align_up(o + p.dp * p.qd * p.esz, ALIGN);
     p.off_ffn_norm = o; o = align_up(o + p.d * 4, ALIGN);
-    p.off_wgu = o; o = align_up(o + 2 * p.F * p.d * p.esz, ALIGN);
-    p.off_wd = o; o = align_up(o + p.d * p.F * p.esz, ALIGN);
+    p.off_wgu = o; o = align_up(o + p.gup * p.d * p.esz, ALIGN);
+    p.off_wd = o; o = align_up(o + p.dp * p.F * p.esz, ALIGN);
     p.layer_bytes = o;
     p.embed_bytes = align_up(p.V * p.d * p.esz, ALIGN);
-    p.lm_bytes = align_up(p.V * p.d * p.esz, ALIGN);
+    p.lm_bytes = align_up(p.Vp * p.d * p.esz, ALIGN);
     p.weights_total = p.layer_bytes * p.L + p.embed_bytes + p.lm_bytes + align_up(p.d * 4, ALIGN);
     // values transposed for the matrix-core attention: every sequence starts on a multiple of 8 columns, plus one
     // key tile of slack so that the last tile of the last sequence can be read whole
@@ -87,10 +94,11 @@ Plan make_plan(const vl_model_cfg& c) {
     p.stage_ints = 12 * p.N + 6 * p.max_tiles + 4 * p.B + 64;
     int64_t w = 0;
     w += align_up(p.N * p.d * 4, ALIGN);                 // residual stream (fp32)
-    w += align_up(p.N * std::max(p.d, p.qd) * p.esz, ALIGN);   // normalised rows / attention output share nothing: two buffers
-    w += align_up(p.N * p.qd * p.esz, ALIGN);            // attention output
+    w += align_up(p.Np * std::max(p.d, p.qd) * p.esz, ALIGN);  // normalised rows / attention output share nothing: two buffers
+    w += align_up(p.Np * p.qd * p.esz, ALIGN);           // attention output
     w += align_up(p.N * p.qkv_w * p.esz, ALIGN);         // q | k | v
-    w += align_up(p.N * p.F * p.esz, ALIGN);             // silu(gate) * up
+    w += align_up(p.Np * p.F * p.esz, ALIGN);            // silu(gate) * up
+    w += align_up(p.wstage_bytes, ALIGN);                // staging for re-tiling weights as they are loaded
     w += align_up(p.N * p.V * 4, ALIGN);                 // logits (fp32)
     if (c.dtype == VL_BF16) w += align_up(p.kvd * p.vt_ld * 2, ALIGN);
     w += 2 * align_up(p.L * p.N * p.kvd * p.esz, ALIGN);   // KV cache of the decode path (packed like the tokens)
@@ -128,6 +136,7 @@ struct vl_ctx {
     char* attn = nullptr;
     char* qkv = nullptr;
     char* act = nullptr;
+    char* wstage = nullptr;             // bf16 models: row-major chunk of a weight tensor on its way to the tiled image
     float* logits = nullptr;
     char* vt = nullptr;
     char* kcache = nullptr;
@@ -297,8 +306,10 @@ bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, bool want_tile
 // bf16 models: every GEMM runs on the matrix cores; up to 64 rows (a decode step) take the weight-streaming kernel,
 // more rows the 256 x 256 tile kernel.  fp32 models: vector-ALU GEMM.
 void gemm(vl_ctx* c, const void* A, const void* W, int M, int N, int K, int epi, void* out) {
-    if (c->bf16 && M <= GEMM_SKINNY_MAX_M) launch_gemm_skinny(A, W, M, N, K, epi, out, c->stream);
-    else if (c->bf16) launch_gemm_mfma(A, W, M, N, K, epi, out, c->stream);
+    // inside the engine every bf16 GEMM operand is a tiled image, and so is the SwiGLU output (the next GEMM's operand)
+    const int layout = GL_A_TILED | GL_W_TILED | (epi == EPI_SWIGLU ? GL_OUT_TILED : 0);
+    if (c->bf16 && M <= GEMM_SKINNY_MAX_M) launch_gemm_skinny(A, W, M, N, K, epi, out, c->stream, layout);
+    else if (c->bf16) launch_gemm_mfma(A, W, M, N, K, epi, out, c->stream, layout);
     else launch_gemm_simple(A, W, c->cfg.dtype, M, N, K, epi, out, (int)c->plan.ib, c->stream);
 }
 
@@ -309,7 +320,7 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
     const LayerW w = layer_w(c, l);
     const int rows = (int)bi.rows;
     hipStream_t s = c->stream;
-    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s); }
+    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16); }
     { StageSpan sp(c, VL_STAGE_QKV_GEMM); gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv); }
     {
         StageSpan sp(c, VL_STAGE_ROPE);
@@ -321,7 +332,7 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
     {
         StageSpan sp(c, VL_STAGE_ATTENTION);
         if (c->bf16) {
-            launch_attn_mfma(c->qkv, rows, c->vt, p.vt_ld, bi.tiles, bi.n_tiles, c->attn, m.n_q_heads, m.n_kv_heads, m.head_dim, s);
+            launch_attn_mfma(c->qkv, rows, c->vt, p.vt_ld, bi.tiles, bi.n_tiles, c->attn, m.n_q_heads, m.n_kv_heads, m.head_dim, s, true);
         } else {
             const char* q = c->qkv;
             launch_attn_rowwise(q, p.qkv_w, q + p.qd * p.esz, q + (p.qd + p.kvd) * p.esz, p.qkv_w, bi.seq_row0, bi.pos, c->attn,
@@ -329,7 +340,7 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
         }
     }
     { StageSpan sp(c, VL_STAGE_O_GEMM); gemm(c, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid); }
-    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s); }
+    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16); }
     { StageSpan sp(c, VL_STAGE_GATEUP_GEMM); gemm(c, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act); }
     { StageSpan sp(c, VL_STAGE_DOWN_GEMM); gemm(c, c->act, w.wd, rows, m.d_model, m.d_ffn, EPI_ADD_RESID, c->resid); }
 }
@@ -341,25 +352,25 @@ void block_decode(vl_ctx* c, int l, int rows, const int32_t* pos, const int32_t*
     const LayerW w = layer_w(c, l);
     hipStream_t s = c->stream;
     const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
-    launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s);
+    launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16);
     gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
     launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s, c->kcache + lo, c->vcache + lo,
                 cache_row);
     if (c->bf16 && attn_decode_supported(m.n_q_heads, m.n_kv_heads, m.head_dim))
         launch_attn_decode(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, rows, m.n_q_heads,
-                           m.n_kv_heads, m.head_dim, s);
+                           m.n_kv_heads, m.head_dim, s, true);
     else
         launch_attn_rowwise(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, m.dtype, rows,
-                            m.n_q_heads, m.n_kv_heads, m.head_dim, s);
+                            m.n_q_heads, m.n_kv_heads, m.head_dim, s, c->bf16);
     gemm(c, c->attn, w.wo, rows, m.d_model, (int)p.qd, EPI_ADD_RESID, c->resid);
-    launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s);
+    launch_rmsnorm(c->resid, w.ffn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16);
     gemm(c, c->xn, w.wgu, rows, 2 * m.d_ffn, m.d_model, EPI_SWIGLU, c->act);
     gemm(c, c->act, w.wd, rows, m.d_model, m.d_ffn, EPI_ADD_RESID, c->resid);
 }
 
 void lm_head_logits(vl_ctx* c, int rows) {
     const vl_model_cfg& m = c->cfg;
-    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, c->final_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, c->stream); }
+    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, c->final_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, c->stream, c->bf16); }
     { StageSpan sp(c, VL_STAGE_LM_GEMM); gemm(c, c->xn, c->lm_head, rows, m.vocab, m.d_model, EPI_STORE_F32, c->logits); }
 }
 
@@ -584,19 +595,21 @@ int vl_create(const vl_model_cfg* cfg, int device, void* hip_stream, vl_ctx** ou
 
     c->layer_slab.resize(p.L, nullptr);
     for (int64_t l = 0; l < p.L; ++l)
-        if ((rc = dev_alloc(c, &c->layer_slab[l], p.layer_bytes, false))) return bail(rc);
+        if ((rc = dev_alloc(c, &c->layer_slab[l], p.layer_bytes, c->bf16))) return bail(rc);   // padding rows of tiled images = 0
     if ((rc = dev_alloc(c, &c->embed, p.embed_bytes, false))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->lm_head, p.lm_bytes, false))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->lm_head, p.lm_bytes, c->bf16))) return bail(rc);
     if ((rc = dev_alloc(c, &c->final_norm, p.d * 4, false))) return bail(rc);
     c->loaded.assign((size_t)p.L * VL_T_COUNT, 0);
     for (int64_t l = 1; l < p.L; ++l)      // the three global tensors are tracked at layer 0 only
         c->loaded[l * VL_T_COUNT + VL_T_EMBED] = c->loaded[l * VL_T_COUNT + VL_T_FINAL_NORM] = c->loaded[l * VL_T_COUNT + VL_T_LM_HEAD] = 1;
 
     if ((rc = dev_alloc(c, &c->resid, p.N * p.d * 4, false))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->xn, p.N * std::max(p.d, p.qd) * p.esz, false))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->attn, p.N * p.qd * p.esz, false))) return bail(rc);
+    // zeroed: rows past the batch (up to the next multiple of 256) are read by the GEMM tiles and must stay finite
+    if ((rc = dev_alloc(c, &c->xn, p.Np * std::max(p.d, p.qd) * p.esz, true))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->attn, p.Np * p.qd * p.esz, true))) return bail(rc);
+    if (p.wstage_bytes && (rc = dev_alloc(c, &c->wstage, p.wstage_bytes, false))) return bail(rc);
     if ((rc = dev_alloc(c, &c->qkv, p.N * p.qkv_w * p.esz, false))) return bail(rc);
-    if ((rc = dev_alloc(c, &c->act, p.N * p.F * p.esz, false))) return bail(rc);
+    if ((rc = dev_alloc(c, &c->act, p.Np * p.F * p.esz, true))) return bail(rc);
     if ((rc = dev_alloc(c, &c->logits, p.N * p.V * 4, false))) return bail(rc);
     if (c->bf16 && (rc = dev_alloc(c, &c->vt, p.kvd * p.vt_ld * 2, true))) return bail(rc);   // zeroed: padding columns are read
     if ((rc = dev_alloc(c, &c->kcache, p.L * p.N * p.kvd * p.esz, false))) return bail(rc);
@@ -674,7 +687,37 @@ int vl_load_weights(vl_ctx* c, int kind, int layer, const void* src, size_t nbyt
         case VL_T_W_DOWN: dst = w.wd; break;
         default: break;
     }
-    if (kind == VL_T_W_GATE || kind == VL_T_W_UP) {
+    const bool matrix = kind != VL_T_EMBED && kind != VL_T_ATTN_NORM && kind != VL_T_FFN_NORM && kind != VL_T_FINAL_NORM;
+    if (c->bf16 && matrix) {
+        // GEMM operands of a bf16 model are stored as tiled images (see tiled_off): the tensor passes through a
+        // row-major staging buffer in chunks of whole 32-row blocks and a kernel scatters each chunk into place
+        int64_t rows = 0, K = 0, row0 = 0;
+        char* image = nullptr;
+        int interleave = 0;
+        switch (kind) {
+            case VL_T_WQ: image = w.wqkv; rows = p.qd; K = p.d; break;                  // fused [q | k | v] rows
+            case VL_T_WK: image = w.wqkv; rows = p.kvd; K = p.d; row0 = p.qd; break;
+            case VL_T_WV: image = w.wqkv; rows = p.kvd; K = p.d; row0 = p.qd + p.kvd; break;
+            case VL_T_WO: image = w.wo; rows = p.d; K = p.qd; break;
+            case VL_T_W_DOWN: image = w.wd; rows = p.d; K = p.F; break;
+            case VL_T_LM_HEAD: image = c->lm_head; rows = p.V; K = p.d; break;
+            // rows interleaved in blocks of 32: [gate 0..32) | up 0..32) | gate 32..64) | ...] so that a GEMM tile holds
+            // gate and up of the same channels and can apply SwiGLU in its epilogue
+            case VL_T_W_GATE: image = w.wgu; rows = p.F; K = p.d; interleave = 1; break;
+            default: image = w.wgu; rows = p.F; K = p.d; interleave = 2; break;
+        }
+        const int64_t row_bytes = K * 2;
+        const int64_t chunk = std::max<int64_t>(32, (p.wstage_bytes / row_bytes) / 32 * 32);
+        if (chunk * row_bytes > p.wstage_bytes) return c->fail(VL_E_CAPACITY, "a 32-row block of this tensor exceeds the staging buffer");
+        for (int64_t r = 0; r < rows; r += chunk) {
+            const int64_t nr = std::min(chunk, rows - r);
+            HIP_TRY(c, hipMemcpyAsync(c->wstage, (const char*)src + r * row_bytes, (size_t)(nr * row_bytes), hipMemcpyDefault, s));
+            // chunks start on multiples of 32 rows, so the interleaving of a chunk is that of its first row plus an offset
+            launch_retile(c->wstage, image, nr, (int)K, interleave ? row0 + 2 * r : row0 + r, interleave, s);
+            HIP_TRY(c, hipGetLastError());
+            HIP_TRY(c, hipStreamSynchronize(s));                // the staging buffer is reused by the next chunk
+        }
+    } else if (kind == VL_T_W_GATE || kind == VL_T_W_UP) {
         // rows interleaved in blocks of ib: [gate 0..ib) | up 0..ib) | gate ib..2ib) | ...] so that a GEMM tile
         // holds gate and up of the same channels and can apply SwiGLU in its epilogue
         const size_t blk = (size_t)(p.ib * p.d * p.esz);

@@ -14,9 +14,14 @@ namespace vl {
 // clears valid[dst ? dst[n] : n] (valid may be NULL); activations therefore stay finite whatever the ids are.
 void launch_embed(const void* E, int dtype, const int32_t* tok, const int32_t* row_tok, float* resid,
                   uint8_t* valid, const int32_t* dst, int64_t rows, int d, int vocab, hipStream_t s);
-// out[n,:] = x[n,:] * rsqrt(mean(x[n,:]^2) + eps) * gain, written in `dtype`.
+// out[n,:] = x[n,:] * rsqrt(mean(x[n,:]^2) + eps) * gain, written in `dtype`; out_tiled: `out` is the tiled image
+// of [rows][d] (see tiled_off) instead of row-major.
 void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int64_t rows, int d, float eps,
-                    hipStream_t s);
+                    hipStream_t s, bool out_tiled = false);
+// dst (tiled image of a [.][K] bf16 matrix) <- rows [0, rows) of src (row-major [rows][K]); source row r lands on row
+// row0 + r, or, with interleave > 0, on row 2*ib*(r/ib) + (interleave == 2 ? ib : 0) + r%ib with ib = 32 (the gate /
+// up interleaving), in both cases counted from row0.
+void launch_retile(const void* src, void* dst, int64_t rows, int K, int64_t row0, int interleave, hipStream_t s);
 // Rotate query and key heads of qkv [rows][(hq+2hkv)*hd] in place using the cos/sin table
 // cs[pos][hd/2] (float2 = cos, sin).  With cache_row != NULL the rotated keys and the values of row n are also
 // copied to row cache_row[n] of kcache / vcache ([cache rows][hkv*hd], same dtype).
@@ -47,12 +52,14 @@ void launch_gemm_simple(const void* A, const void* W, int dtype, int M, int N, i
 // ---- bf16 matrix-core GEMM (kernels_gemm_mfma.hip) -----------------------------------------------
 // Same contract as launch_gemm_simple with dtype = bf16; K % 64 == 0; EPI_SWIGLU interleaves in blocks of 32
 // rows and needs N % 64 == 0.
-void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s);
+// layout: bit 0 = A is a tiled image, bit 1 = W is, bit 2 = the SwiGLU output is written as one (see tiled_off).
+enum GemmLayout { GL_A_TILED = 1, GL_W_TILED = 2, GL_OUT_TILED = 4 };
+void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout = 0);
 
 // ---- bf16 weight-streaming GEMM for M <= 64 rows (kernels_gemm_skinny.hip) --------------------------
 // Same contract; K % 32 == 0; EPI_SWIGLU needs N % 64 == 0.
 constexpr int GEMM_SKINNY_MAX_M = 64;
-void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s);
+void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout = 0);
 
 // ---- attention ------------------------------------------------------------------------------------
 // One wave per (query row, query head), online softmax over keys 0..npos[row].
@@ -60,14 +67,14 @@ void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int e
 //   k, v : key/value t of row r, kv head g at  base[(kv_row0[r] + t) * kv_stride + g*hd]
 void launch_attn_rowwise(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                          const int32_t* kv_row0, const int32_t* npos, void* out, int dtype, int64_t rows, int hq,
-                         int hkv, int hd, hipStream_t s);
+                         int hkv, int hd, hipStream_t s, bool out_tiled = false);
 
 // bf16, one workgroup per (query row, KV head), all query heads of the group together (kernels_attn_decode.hip).
 // Same addressing as launch_attn_rowwise; needs head_dim 64 or 128 and Hq / Hkv in {1, 2, 4, 8}.
 bool attn_decode_supported(int hq, int hkv, int hd);
 void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                         const int32_t* kv_row0, const int32_t* npos, void* out, int64_t rows, int hq, int hkv, int hd,
-                        hipStream_t s);
+                        hipStream_t s, bool out_tiled = false);
 // Causal GQA flash attention on the matrix cores over packed sequences.
 //   qkv bf16 [N][(hq+2hkv)*hd], vt bf16 [hkv][hd][ldv] (values transposed, column = vt column of the token),
 //   tiles: host-built work list (see engine), out bf16 [N][hq*hd].
@@ -76,7 +83,7 @@ struct AttnTile { int32_t q_row0, q_rows, kv_row0, kv_len, vt_col0, pos0; };  //
 //   kv_row0 packed row of the sequence's first token, kv_len = pos0 + q_rows keys are visible to the tile,
 //   vt_col0 column of the sequence's first token in vt (a multiple of 8)
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
-                      void* out, int hq, int hkv, int hd, hipStream_t s);
+                      void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled = false);
 
 // ---- compare / argmax / flags (kernels_compare.hip) ------------------------------------------------
 void launch_compare(const float* h_hat, const void* committed, int hidden_dtype, int64_t rows, int d, float tol_rel,

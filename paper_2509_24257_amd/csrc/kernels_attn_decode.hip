@@ -38,7 +38,7 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
                                                                  const bf16* __restrict__ k, const bf16* __restrict__ v,
                                                                  int64_t kv_stride, const int32_t* __restrict__ kv_row0,
                                                                  const int32_t* __restrict__ npos, bf16* __restrict__ out,
-                                                                 int hq, float scale) {
+                                                                 int hq, float scale, bool out_tiled) {
     constexpr int LPK = HD / 8;                                 // lanes per key row
     constexpr int KPP = WAVE / LPK;                             // keys per pass
     constexpr int DPL = HD / WAVE;                              // value channels per lane
@@ -164,7 +164,8 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
             num = fmaf(part_o[w][g][d], f, num);
             den = fmaf(part_l[w][g], f, den);
         }
-        out[row * (int64_t)hq * HD + (int64_t)(kvh * G + g) * HD + d] = (bf16)(num / den);
+        const int col = (kvh * G + g) * HD + d;
+        out[out_tiled ? tiled_off(row, col, (int64_t)hq * HD) : row * (int64_t)hq * HD + col] = (bf16)(num / den);
     }
 }
 
@@ -175,25 +176,25 @@ bool attn_decode_supported(int hq, int hkv, int hd) {
 
 template <int G>
 static void launch_g(const bf16* q, int64_t q_stride, const bf16* k, const bf16* v, int64_t kv_stride, const int32_t* kv_row0,
-                     const int32_t* npos, bf16* out, int64_t rows, int hq, int hkv, int hd, hipStream_t s) {
+                     const int32_t* npos, bf16* out, int64_t rows, int hq, int hkv, int hd, hipStream_t s, bool out_tiled) {
     const float scale = 1.0f / sqrtf((float)hd);
     dim3 grid((unsigned)rows, (unsigned)hkv);
     if (hd == 64)
-        attn_decode_kernel<G, 64><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale);
+        attn_decode_kernel<G, 64><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale, out_tiled);
     else
-        attn_decode_kernel<G, 128><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale);
+        attn_decode_kernel<G, 128><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale, out_tiled);
 }
 
 void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                         const int32_t* kv_row0, const int32_t* npos, void* out, int64_t rows, int hq, int hkv, int hd,
-                        hipStream_t s) {
+                        hipStream_t s, bool out_tiled) {
     if (rows <= 0) return;
     const bf16 *qq = (const bf16*)q, *kk = (const bf16*)k, *vv = (const bf16*)v;
     switch (hq / hkv) {
-        case 1: launch_g<1>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
-        case 2: launch_g<2>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
-        case 4: launch_g<4>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
-        default: launch_g<8>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s); break;
+        case 1: launch_g<1>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;
+        case 2: launch_g<2>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;
+        case 4: launch_g<4>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;
+        default: launch_g<8>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;
     }
 }
 

@@ -29,7 +29,8 @@ template <int HD>
 __global__ __launch_bounds__(FA_THREADS) void attn_mfma_kernel(const bf16* __restrict__ qkv, int64_t n_rows,
                                                                const bf16* __restrict__ vt, int64_t ldv,
                                                                const AttnTile* __restrict__ tiles,
-                                                               bf16* __restrict__ out, int hq, int hkv, float scale_log2e) {
+                                                               bf16* __restrict__ out, int hq, int hkv, float scale_log2e,
+                                                               bool out_tiled) {
     constexpr int KP = HD + 8;               // K tile row pitch (elements)
     constexpr int VP = FA_BK + 8;            // V^T tile row pitch
     constexpr int KSTEPS = HD / 16;          // MFMA k-steps over the head dimension
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(FA_THREADS) void attn_mfma_kernel(const bf16* __res
     const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
     const float inv = 1.0f / l_tot;
     if (q_local < t.q_rows) {
-        bf16* op = out + (int64_t)(t.q_row0 + q_local) * hq * HD + (int64_t)head * HD;
+        const int64_t orow = t.q_row0 + q_local;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -164,22 +165,23 @@ __global__ __launch_bounds__(FA_THREADS) void attn_mfma_kernel(const bf16* __res
                 bf16x4 v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[b][rg * 4 + e] * inv);
-                *(bf16x4*)(op + b * 32 + rg * 8 + half * 4) = v;
+                const int col = head * HD + b * 32 + rg * 8 + half * 4;            // 4 | 32: never straddles a piece
+                *(bf16x4*)(out + (out_tiled ? tiled_off(orow, col, (int64_t)hq * HD) : orow * hq * HD + col)) = v;
             }
     }
 }
 
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
-                      void* out, int hq, int hkv, int hd, hipStream_t s) {
+                      void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled) {
     if (n_tiles <= 0) return;
     const float scale_log2e = (1.0f / sqrtf((float)hd)) * 1.4426950408889634f;
     dim3 grid((unsigned)n_tiles, (unsigned)hq);
     if (hd == 128)
         attn_mfma_kernel<128><<<grid, FA_THREADS, 0, s>>>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, (bf16*)out, hq,
-                                                          hkv, scale_log2e);
+                                                          hkv, scale_log2e, out_tiled);
     else
         attn_mfma_kernel<64><<<grid, FA_THREADS, 0, s>>>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, (bf16*)out, hq,
-                                                         hkv, scale_log2e);
+                                                         hkv, scale_log2e, out_tiled);
 }
 
 }  // namespace vl

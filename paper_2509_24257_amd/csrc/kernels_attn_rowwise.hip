@@ -22,7 +22,7 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
                                                           const T* __restrict__ k, const T* __restrict__ v,
                                                           int64_t kv_stride, const int32_t* __restrict__ kv_row0,
                                                           const int32_t* __restrict__ npos, T* __restrict__ out,
-                                                          int hq, int hkv, int hd, float scale) {
+                                                          int hq, int hkv, int hd, float scale, bool out_tiled) {
     __shared__ float qs[256];
     const int64_t row = blockIdx.x;
     const int j = blockIdx.y, g = j / (hq / hkv), lane = threadIdx.x;
@@ -70,22 +70,22 @@ __global__ __launch_bounds__(64) void attn_rowwise_kernel(const T* __restrict__ 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int c = lane + WAVE * i;
-        if (c < hd) out[row * (int64_t)hq * hd + (int64_t)j * hd + c] = from_f32<T>(o[i] * inv);
+        if (c < hd) out[out_tiled ? tiled_off(row, j * hd + c, (int64_t)hq * hd) : row * (int64_t)hq * hd + (int64_t)j * hd + c] = from_f32<T>(o[i] * inv);
     }
 }
 
 void launch_attn_rowwise(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
                          const int32_t* kv_row0, const int32_t* npos, void* out, int dtype, int64_t rows, int hq,
-                         int hkv, int hd, hipStream_t s) {
+                         int hkv, int hd, hipStream_t s, bool out_tiled) {
     if (rows <= 0) return;
     const float scale = 1.0f / sqrtf((float)hd);
     dim3 grid((unsigned)rows, (unsigned)hq);
     if (dtype == VL_BF16)
         attn_rowwise_kernel<bf16><<<grid, 64, 0, s>>>((const bf16*)q, q_stride, (const bf16*)k, (const bf16*)v, kv_stride,
-                                                      kv_row0, npos, (bf16*)out, hq, hkv, hd, scale);
+                                                      kv_row0, npos, (bf16*)out, hq, hkv, hd, scale, out_tiled);
     else
         attn_rowwise_kernel<float><<<grid, 64, 0, s>>>((const float*)q, q_stride, (const float*)k, (const float*)v,
-                                                       kv_stride, kv_row0, npos, (float*)out, hq, hkv, hd, scale);
+                                                       kv_stride, kv_row0, npos, (float*)out, hq, hkv, hd, scale, false);
 }
 
 }  // namespace vl

@@ -53,7 +53,7 @@ constexpr int GM_WAIT_VM0_LGKM0 = 0x0070;                       // vmcnt(0)  lgk
 template <int EPI>
 __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                                                                   int M, int N, int K, void* __restrict__ outp,
-                                                                  int tiles_m, int tiles_n) {
+                                                                  int tiles_m, int tiles_n, int layout) {
     __shared__ __align__(1024) unsigned char ring[GM_SLOTS * GM_SLOT];
 
     // ---- XCD-aware tile order
@@ -76,14 +76,17 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
     // ---- direct-to-LDS sources.  Load i (0,1) of this wave fills LDS rows 16*(wave + 8 i) .. +15 of an operand:
     // lane -> (row = 16*(wave + 8 i) + lane/4, physical chunk = lane%4), which must hold logical chunk
     // phys ^ ((row/4)%4).  Rows past the matrix edge re-read the last row (their results are never stored).
+    // A tiled operand (see tiled_off) is padded to whole 256-row blocks and its k-tiles are 16 KB apart.
     const bf16* ga[2];
     const bf16* gw[2];
+    const int a_step = (layout & GL_A_TILED) ? TL_PIECE : GM_BK;        // elements between consecutive k-tiles
+    const int w_step = (layout & GL_W_TILED) ? TL_PIECE : GM_BK;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = 16 * (wave + 8 * i) + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 2) & 3);
-        ga[i] = A + (int64_t)min(m0 + row, M - 1) * K + c * 8;
-        gw[i] = W + (int64_t)min(n0 + row, N - 1) * K + c * 8;
+        ga[i] = (layout & GL_A_TILED) ? A + tiled_off(m0 + row, 0, K) + c * 8 : A + (int64_t)min(m0 + row, M - 1) * K + c * 8;
+        gw[i] = (layout & GL_W_TILED) ? W + tiled_off(n0 + row, 0, K) + c * 8 : W + (int64_t)min(n0 + row, N - 1) * K + c * 8;
     }
     const int dma_off = wave * 1024;                            // + i * 8192, + GM_OPER for W
 
@@ -110,10 +113,10 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 #define GM_DMA_TILE(SLOT, KTILE)                                                                              \
     {                                                                                                         \
         unsigned char* dst_ = ring + (SLOT) * GM_SLOT + dma_off;                                              \
-        __builtin_amdgcn_global_load_lds(GM_GLB(ga[0] + (KTILE) * GM_BK), GM_LDS(dst_), 16, 0, 0);            \
-        __builtin_amdgcn_global_load_lds(GM_GLB(gw[0] + (KTILE) * GM_BK), GM_LDS(dst_ + GM_OPER), 16, 0, 0);  \
-        __builtin_amdgcn_global_load_lds(GM_GLB(ga[1] + (KTILE) * GM_BK), GM_LDS(dst_ + 8192), 16, 0, 0);     \
-        __builtin_amdgcn_global_load_lds(GM_GLB(gw[1] + (KTILE) * GM_BK), GM_LDS(dst_ + GM_OPER + 8192), 16, 0, 0); \
+        __builtin_amdgcn_global_load_lds(GM_GLB(ga[0] + (int64_t)(KTILE) * a_step), GM_LDS(dst_), 16, 0, 0);  \
+        __builtin_amdgcn_global_load_lds(GM_GLB(gw[0] + (int64_t)(KTILE) * w_step), GM_LDS(dst_ + GM_OPER), 16, 0, 0); \
+        __builtin_amdgcn_global_load_lds(GM_GLB(ga[1] + (int64_t)(KTILE) * a_step), GM_LDS(dst_ + 8192), 16, 0, 0); \
+        __builtin_amdgcn_global_load_lds(GM_GLB(gw[1] + (int64_t)(KTILE) * w_step), GM_LDS(dst_ + GM_OPER + 8192), 16, 0, 0); \
     }
 
     // ---- prologue: tiles 0 .. 3 into slots 0 .. 3, everything landed and published
@@ -171,11 +174,14 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
             const int mb = m0 + grp * 128 + i * 32 + row_half;
             if (EPI == EPI_SWIGLU) {
                 const int F = N >> 1;
-                bf16* out = (bf16*)outp + (int64_t)mb * F + ((n0 + wn * 64) >> 1) + col_in;
+                const int f = ((n0 + wn * 64) >> 1) + col_in;
+                // row-major: rows F apart; tiled: the 32 channels of this block sit in one piece, rows 32 elements apart
+                bf16* out = (bf16*)outp + ((layout & GL_OUT_TILED) ? tiled_off(mb, f, F) : (int64_t)mb * F + f);
+                const int64_t rs = (layout & GL_OUT_TILED) ? TL_K : F;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float g = acc[i][0][r], u = acc[i][1][r];
-                    out[(int64_t)((r >> 2) * 8 + (r & 3)) * F] = (bf16)(g / (1.0f + __expf(-g)) * u);
+                    out[(int64_t)((r >> 2) * 8 + (r & 3)) * rs] = (bf16)(g / (1.0f + __expf(-g)) * u);
                 }
             } else {
 #pragma unroll
@@ -217,7 +223,7 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
                     const int m = mb + (r >> 2) * 8 + (r & 3);
                     if (m < M) {
                         const float g = acc[i][0][r], u = acc[i][1][r];
-                        out[(int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
+                        out[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
                     }
                 }
             }
@@ -241,22 +247,22 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 }
 
 template <int EPI>
-static void launch_one(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s) {
+static void launch_one(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s, int layout) {
     const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (N + GM_BN - 1) / GM_BN;
     const int total = tiles_m * tiles_n;
     const int grid = ((total + GM_XCDS - 1) / GM_XCDS) * GM_XCDS;
-    gemm_mfma_kernel<EPI><<<dim3((unsigned)grid), GM_THREADS, 0, s>>>(A, W, M, N, K, out, tiles_m, tiles_n);
+    gemm_mfma_kernel<EPI><<<dim3((unsigned)grid), GM_THREADS, 0, s>>>(A, W, M, N, K, out, tiles_m, tiles_n, layout);
 }
 
-void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s) {
+void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout) {
     if (M <= 0 || N <= 0) return;
     const bf16* a = (const bf16*)A;
     const bf16* w = (const bf16*)W;
     switch (epi) {
-        case EPI_STORE: launch_one<EPI_STORE>(a, w, M, N, K, out, s); break;
-        case EPI_STORE_F32: launch_one<EPI_STORE_F32>(a, w, M, N, K, out, s); break;
-        case EPI_ADD_RESID: launch_one<EPI_ADD_RESID>(a, w, M, N, K, out, s); break;
-        default: launch_one<EPI_SWIGLU>(a, w, M, N, K, out, s); break;
+        case EPI_STORE: launch_one<EPI_STORE>(a, w, M, N, K, out, s, layout); break;
+        case EPI_STORE_F32: launch_one<EPI_STORE_F32>(a, w, M, N, K, out, s, layout); break;
+        case EPI_ADD_RESID: launch_one<EPI_ADD_RESID>(a, w, M, N, K, out, s, layout); break;
+        default: launch_one<EPI_SWIGLU>(a, w, M, N, K, out, s, layout); break;
     }
 }
 

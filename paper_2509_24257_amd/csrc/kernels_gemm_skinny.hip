@@ -23,7 +23,7 @@ constexpr int GS_WAVES = 8;
 
 template <int EPI, int MT, int NG>
 __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
-                                                                 int M, int N, int K, void* __restrict__ outp) {
+                                                                 int M, int N, int K, void* __restrict__ outp, int layout) {
     static_assert(EPI != EPI_SWIGLU || NG == 2, "SwiGLU pairs a gate group with an up group");
     __shared__ __align__(16) float red[GS_WAVES][NG * MT * 256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -38,11 +38,18 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
         r0 = blockIdx.x * (16 * NG);
         r1 = r0 + 16;
     }
-    const bf16* w0 = W + (int64_t)min(r0 + fr, N - 1) * K + fq * 8;
-    const bf16* w1 = W + (int64_t)min(r1 + fr, N - 1) * K + fq * 8;
+    // operands are row-major or tiled images (see tiled_off); a k-step of 32 is then 32 or 8192 elements further on
+    const bool wt = layout & GL_W_TILED, at = layout & GL_A_TILED;
+    const int64_t w_step = wt ? TL_PIECE : 32, a_step = at ? TL_PIECE : 32;
+    const int wr0 = min(r0 + fr, N - 1), wr1 = min(r1 + fr, N - 1);
+    const bf16* w0 = W + (wt ? tiled_off(wr0, 0, K) : (int64_t)wr0 * K) + fq * 8;
+    const bf16* w1 = W + (wt ? tiled_off(wr1, 0, K) : (int64_t)wr1 * K) + fq * 8;
     const bf16* ap[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) ap[t] = A + (int64_t)min(t * 16 + fr, M - 1) * K + fq * 8;
+    for (int t = 0; t < MT; ++t) {
+        const int ar = min(t * 16 + fr, M - 1);
+        ap[t] = A + (at ? tiled_off(ar, 0, K) : (int64_t)ar * K) + fq * 8;
+    }
 
     f32x4 acc[NG][MT];
 #pragma unroll
@@ -57,11 +64,11 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
         bf16x8 a0[4], a1[4], b[MT][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int o = (ks + u) * 32;
-            a0[u] = *(const bf16x8*)(w0 + o);
-            if (NG == 2) a1[u] = *(const bf16x8*)(w1 + o);
+            const int64_t ow = (ks + u) * w_step, oa = (ks + u) * a_step;
+            a0[u] = *(const bf16x8*)(w0 + ow);
+            if (NG == 2) a1[u] = *(const bf16x8*)(w1 + ow);
 #pragma unroll
-            for (int t = 0; t < MT; ++t) b[t][u] = *(const bf16x8*)(ap[t] + o);
+            for (int t = 0; t < MT; ++t) b[t][u] = *(const bf16x8*)(ap[t] + oa);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -72,11 +79,11 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
             }
     }
     for (; ks < ke; ++ks) {
-        const int o = ks * 32;
-        const bf16x8 a0 = *(const bf16x8*)(w0 + o), a1 = *(const bf16x8*)((NG == 2 ? w1 : w0) + o);
+        const int64_t ow = ks * w_step, oa = ks * a_step;
+        const bf16x8 a0 = *(const bf16x8*)(w0 + ow), a1 = *(const bf16x8*)((NG == 2 ? w1 : w0) + ow);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            const bf16x8 b = *(const bf16x8*)(ap[t] + o);
+            const bf16x8 b = *(const bf16x8*)(ap[t] + oa);
             acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][t], 0, 0, 0);
             if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[NG - 1][t], 0, 0, 0);
         }
@@ -100,7 +107,8 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
             }
             const int l = (e & 255) >> 2, r = e & 3;
             const int m = (e >> 8) * 16 + (l & 15), f = ch0 + 4 * (l >> 4) + r;
-            if (m < M && f < F) ((bf16*)outp)[(int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
+            if (m < M && f < F)
+                ((bf16*)outp)[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
         }
     } else {
         for (int e = threadIdx.x; e < NG * PER_GROUP; e += GS_THREADS) {
@@ -121,29 +129,29 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
 }
 
 template <int EPI, int NG>
-static void launch_mt(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s) {
+static void launch_mt(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s, int layout) {
     const unsigned grid = (unsigned)((N + 16 * NG - 1) / (16 * NG));
-    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
-    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
-    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out);
+    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout);
+    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout);
+    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout);
 }
 
 // one row group per workgroup while two would leave fewer than two workgroups per compute unit
 template <int EPI>
-static void launch_ng(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s) {
-    if (EPI == EPI_SWIGLU || N >= 32 * 512) launch_mt<EPI, 2>(A, W, M, N, K, out, s);
-    else launch_mt<EPI == EPI_SWIGLU ? EPI_STORE : EPI, 1>(A, W, M, N, K, out, s);
+static void launch_ng(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s, int layout) {
+    if (EPI == EPI_SWIGLU || N >= 32 * 512) launch_mt<EPI, 2>(A, W, M, N, K, out, s, layout);
+    else launch_mt<EPI == EPI_SWIGLU ? EPI_STORE : EPI, 1>(A, W, M, N, K, out, s, layout);
 }
 
-void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s) {
+void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout) {
     if (M <= 0 || N <= 0) return;
     const bf16* a = (const bf16*)A;
     const bf16* w = (const bf16*)W;
     switch (epi) {
-        case EPI_STORE: launch_ng<EPI_STORE>(a, w, M, N, K, out, s); break;
-        case EPI_STORE_F32: launch_ng<EPI_STORE_F32>(a, w, M, N, K, out, s); break;
-        case EPI_ADD_RESID: launch_ng<EPI_ADD_RESID>(a, w, M, N, K, out, s); break;
-        default: launch_ng<EPI_SWIGLU>(a, w, M, N, K, out, s); break;
+        case EPI_STORE: launch_ng<EPI_STORE>(a, w, M, N, K, out, s, layout); break;
+        case EPI_STORE_F32: launch_ng<EPI_STORE_F32>(a, w, M, N, K, out, s, layout); break;
+        case EPI_ADD_RESID: launch_ng<EPI_ADD_RESID>(a, w, M, N, K, out, s, layout); break;
+        default: launch_ng<EPI_SWIGLU>(a, w, M, N, K, out, s, layout); break;
     }
 }
 

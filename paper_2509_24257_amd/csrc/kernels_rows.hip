@@ -1,6 +1,8 @@
 // Row-wise HBM-bound kernels of the decoder block: embedding gather, RMSNorm, rotary embedding, value
 // transpose, KV-cache store, hidden-state store.  One workgroup (256 lanes = 4 waves) per token row unless
 // noted; loads and stores are contiguous along the row so each wave touches whole cache lines.
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -49,9 +51,16 @@ void launch_embed(const void* E, int dtype, const int32_t* tok, const int32_t* r
 }
 
 // ---------------------------------------------------------------- RMSNorm
+__device__ __forceinline__ void store4(float* o, float a, float b, float c, float d) { *(float4*)o = make_float4(a, b, c, d); }
+__device__ __forceinline__ void store4(bf16* o, float a, float b, float c, float d) {
+    bf16x4 t;
+    t[0] = (bf16)a; t[1] = (bf16)b; t[2] = (bf16)c; t[3] = (bf16)d;
+    *(bf16x4*)o = t;
+}
+
 template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                               T* __restrict__ out, int d, float eps) {
+                                                               T* __restrict__ out, int d, float eps, bool out_tiled) {
     __shared__ float red[ROW_THREADS / WAVE];
     const int64_t n = blockIdx.x;
     const float4* xr = (const float4*)(x + n * (int64_t)d);
@@ -64,24 +73,42 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __res
     }
     ss = block_sum(ss, red);
     const float r = 1.0f / sqrtf(ss / (float)d + eps);
-    T* o = out + n * (int64_t)d;
     for (int i = threadIdx.x; i < d4; i += ROW_THREADS) {
         const float4 v = xr[i];
         const float4 g = g4[i];
-        o[4 * i + 0] = from_f32<T>(v.x * r * g.x);
-        o[4 * i + 1] = from_f32<T>(v.y * r * g.y);
-        o[4 * i + 2] = from_f32<T>(v.z * r * g.z);
-        o[4 * i + 3] = from_f32<T>(v.w * r * g.w);
+        T* o = out + (out_tiled ? tiled_off(n, 4 * i, d) : n * (int64_t)d + 4 * i);    // 4 | 32: a quad never straddles a piece
+        store4(o, v.x * r * g.x, v.y * r * g.y, v.z * r * g.z, v.w * r * g.w);
     }
 }
 
 void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int64_t rows, int d, float eps,
-                    hipStream_t s) {
+                    hipStream_t s, bool out_tiled) {
     if (rows <= 0) return;
     if (dtype == VL_BF16)
-        rmsnorm_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (bf16*)out, d, eps);
+        rmsnorm_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (bf16*)out, d, eps, out_tiled);
     else
-        rmsnorm_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (float*)out, d, eps);
+        rmsnorm_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (float*)out, d, eps, false);
+}
+
+// ---------------------------------------------------------------- row-major -> tiled image (weights, at load time)
+__global__ __launch_bounds__(256) void retile_kernel(const bf16* __restrict__ src, bf16* __restrict__ dst, int64_t rows, int K,
+                                                     int64_t row0, int interleave) {
+    const int k8 = K >> 3;                                      // 16-byte chunks per row
+    const int64_t total = rows * k8;
+    for (int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x; id < total; id += (int64_t)gridDim.x * 256) {
+        const int64_t r = id / k8;
+        const int c = (int)(id - r * k8);
+        int64_t dr = row0 + r;
+        if (interleave) dr = row0 + 64 * (r >> 5) + (interleave == 2 ? 32 : 0) + (r & 31);
+        *(u32x4*)(dst + tiled_off(dr, 8 * c, K)) = *(const u32x4*)(src + r * K + 8 * c);
+    }
+}
+
+void launch_retile(const void* src, void* dst, int64_t rows, int K, int64_t row0, int interleave, hipStream_t s) {
+    if (rows <= 0) return;
+    const int64_t total = rows * (K >> 3);
+    const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
+    retile_kernel<<<grid, 256, 0, s>>>((const bf16*)src, (bf16*)dst, rows, K, row0, interleave);
 }
 
 // ---------------------------------------------------------------- rotary embedding, in place on Q and K

@@ -18,6 +18,20 @@ from oracle import verillm_oracle as O
 DEV = "cuda:0"
 
 
+CAPTURE_MANAGER = None      # set by conftest.py
+
+
+def progress(msg: str):
+    """One line that names the step about to run, written past pytest's output capture: a long GPU test must show
+    what it is doing while it runs (a faulting kernel can take the captured text with it, and a quiet run looks hung)."""
+    cm = CAPTURE_MANAGER
+    if cm is not None:
+        with cm.global_and_fixture_disabled():
+            print(msg, flush=True)
+    else:
+        print(msg, flush=True)
+
+
 def c_cfg(m: synth.ModelCfg, max_tokens: int, max_seqs: int, max_seq_len: int) -> P.ModelCfg:
     return P.ModelCfg(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab, m.rms_eps,
                       m.rope_base, P.VL_BF16 if m.dtype == "bf16" else P.VL_F32, max_tokens, max_seqs, max_seq_len)
@@ -51,7 +65,7 @@ def oracle_model(m: synth.ModelCfg, override=None, progress: str = "", operand_d
 
     def w(kind, layer):
         if progress and kind == synth.ATTN_NORM and layer % 8 == 0:
-            print("[oracle %s] layer %d/%d" % (progress, layer, m.n_layers), flush=True)
+            globals()["progress"]("[oracle %s] layer %d/%d" % (progress, layer, m.n_layers))
         if (kind, layer) in override:
             return override[(kind, layer)]
         return synth.weight(m, kind, layer, 16)

@@ -23,8 +23,7 @@ pytestmark = pytest.mark.gpu
 
 
 def say(msg):
-    print("[case] " + msg, flush=True)
-    sys.stdout.flush()
+    H.progress("[case] " + msg)
 
 
 def oracle_commitments(om, wl, x, mode="prefill"):

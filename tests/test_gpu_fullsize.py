@@ -30,8 +30,7 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
 
 def say(msg):
-    print("[case] " + msg, flush=True)
-    sys.stdout.flush()
+    H.progress("[case] " + msg)
 
 
 @pytest.fixture(scope="module")

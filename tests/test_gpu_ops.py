@@ -15,8 +15,7 @@ pytestmark = pytest.mark.gpu
 
 
 def say(msg):
-    print("[case] " + msg, flush=True)
-    sys.stdout.flush()
+    H.progress("[case] " + msg)
 
 
 @pytest.fixture(scope="module")
