@@ -26,7 +26,7 @@ constexpr int FA_BK = 64;         // keys per step
 constexpr int FA_THREADS = 256;
 
 template <int HD>
-__global__ __launch_bounds__(FA_THREADS) void attn_mfma_kernel(const bf16* __restrict__ qkv, int64_t n_rows,
+__global__ __launch_bounds__(FA_THREADS, 2) void attn_mfma_kernel(const bf16* __restrict__ qkv, int64_t n_rows,
                                                                const bf16* __restrict__ vt, int64_t ldv,
                                                                const AttnTile* __restrict__ tiles,
                                                                bf16* __restrict__ out, int hq, int hkv, float scale_log2e,
@@ -65,25 +65,46 @@ __global__ __launch_bounds__(FA_THREADS) void attn_mfma_kernel(const bf16* __res
     const int n_kv_tiles = (t.kv_len + FA_BK - 1) / FA_BK;
     const int wave_first_pos = t.pos0 + wave * 32;
 
-    for (int kt = 0; kt < n_kv_tiles; ++kt) {
-        const int key0 = kt * FA_BK;
-        __syncthreads();                                         // everyone is done with the previous tiles
+    // The tiles travel global -> registers -> LDS; the registers of tile kt+1 are requested right after tile kt has been
+    // published in LDS, so the memory latency runs behind the arithmetic of tile kt.
+    constexpr int KLD = (FA_BK * HD / 8) / FA_THREADS, VLD = (HD * FA_BK / 8) / FA_THREADS;
+    u32x4 kreg[KLD], vreg[VLD];
+    auto fetch = [&](int key0) {
         // K tile: 64 rows x HD, 16-byte chunks; rows past the end of the buffer re-read the last row (masked below)
 #pragma unroll
-        for (int i = 0; i < (FA_BK * HD / 8) / FA_THREADS; ++i) {
+        for (int i = 0; i < KLD; ++i) {
             const int id = tid + FA_THREADS * i;
             const int row = id / (HD / 8), c = id % (HD / 8);
             const int64_t grow = min((int64_t)t.kv_row0 + key0 + row, n_rows - 1);
-            *(uint4*)(ks + row * KP + c * 8) = *(const uint4*)(kbase + grow * pitch + c * 8);
+            kreg[i] = *(const u32x4*)(kbase + grow * pitch + c * 8);
         }
         // V^T tile: HD rows x 64 keys (the vt buffer is padded, so the columns always exist)
 #pragma unroll
-        for (int i = 0; i < (HD * FA_BK / 8) / FA_THREADS; ++i) {
+        for (int i = 0; i < VLD; ++i) {
             const int id = tid + FA_THREADS * i;
             const int row = id >> 3, c = id & 7;
-            *(uint4*)(vs + row * VP + c * 8) = *(const uint4*)(vbase + (int64_t)row * ldv + key0 + c * 8);
+            vreg[i] = *(const u32x4*)(vbase + (int64_t)row * ldv + key0 + c * 8);
+        }
+    };
+    fetch(0);
+    const int wave_last_pos = t.pos0 + min(wave * 32 + 31, t.q_rows - 1);
+
+    for (int kt = 0; kt < n_kv_tiles; ++kt) {
+        const int key0 = kt * FA_BK;
+        __syncthreads();                                         // everyone is done with the previous tiles
+#pragma unroll
+        for (int i = 0; i < KLD; ++i) {
+            const int id = tid + FA_THREADS * i;
+            *(u32x4*)(ks + (id / (HD / 8)) * KP + (id % (HD / 8)) * 8) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VLD; ++i) {
+            const int id = tid + FA_THREADS * i;
+            *(u32x4*)(vs + (id >> 3) * VP + (id & 7) * 8) = vreg[i];
         }
         __syncthreads();
+        if (kt + 1 < n_kv_tiles) fetch(key0 + FA_BK);
+        if (key0 > wave_last_pos) continue;                      // uniform per wave: every key of the tile is masked
 
         // ---- S^T = K Q^T for the two 32-key blocks of this tile
         f32x16 st[2];
