@@ -91,7 +91,7 @@ Plan make_plan(const vl_model_cfg& c) {
     // key tile of slack so that the last tile of the last sequence can be read whole
     p.vt_ld = align_up(p.N + 8 * p.B + 64, 64);
     p.max_tiles = p.N / 128 + p.B + 1;
-    p.stage_ints = 12 * p.N + 6 * p.max_tiles + 4 * p.B + 64;
+    p.stage_ints = 12 * p.N + 6 * p.max_tiles + 8 * p.B + 64;
     int64_t w = 0;
     w += align_up(p.N * p.d * 4, ALIGN);                 // residual stream (fp32)
     w += align_up(p.Np * std::max(p.d, p.qd) * p.esz, ALIGN);  // normalised rows / attention output share nothing: two buffers
@@ -122,6 +122,8 @@ struct vl_ctx {
     Plan plan{};
     int device = 0;
     hipStream_t stream = nullptr;
+    bool capturing = false;             // a decode step is being recorded as a graph: no timing events
+    bool own_stream = false;            // created here because the caller passed none (graphs cannot be captured on the NULL stream)
     std::string err;
     bool bf16 = false;
 
@@ -180,7 +182,7 @@ namespace {
 struct StageSpan {
     vl_ctx* c; bool on = false; vl_ctx::Span sp{};
     StageSpan(vl_ctx* c_, int stage) : c(c_) {
-        if (c->prof_mode == 0 || (c->prof_mode == 1 && stage != VL_STAGE_GATEUP_GEMM)) return;
+        if (c->prof_mode == 0 || (c->prof_mode == 1 && stage != VL_STAGE_GATEUP_GEMM) || c->capturing) return;
         if (c->prof_used + 2 > c->prof_pool.size()) return;
         sp.stage = stage; sp.a = c->prof_pool[c->prof_used++]; sp.b = c->prof_pool[c->prof_used++];
         on = hipEventRecord(sp.a, c->stream) == hipSuccess;
@@ -567,6 +569,7 @@ void vl_destroy(vl_ctx* ctx) {
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->h_idx) (void)hipHostFree(ctx->h_idx);
     if (ctx->h_summary) (void)hipHostFree(ctx->h_summary);
+    if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
     delete ctx;
 }
 
@@ -588,6 +591,13 @@ int vl_create(const vl_model_cfg* cfg, int device, void* hip_stream, vl_ctx** ou
     c->plan = make_plan(*cfg);
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
+    if (!c->stream) {
+        // default flags and default priority: the stream still orders itself against the NULL stream, like the NULL
+        // stream itself would, so callers that produce inputs there need no extra synchronisation
+        e = hipStreamCreate(&c->stream);
+        if (e != hipSuccess) { g_create_error = fmt("hipStreamCreate failed: %s", hipGetErrorString(e)); delete c; return VL_E_HIP; }
+        c->own_stream = true;
+    }
     c->bf16 = cfg->dtype == VL_BF16;
     const Plan& p = c->plan;
     int rc = VL_OK;
@@ -832,6 +842,9 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
     if (!st.take(nd, &h_dsrc, &d_dsrc) || !st.take(nd, &h_dpos, &d_dpos) || !st.take(nd, &h_dcrow, &d_dcrow) ||
         !st.take(nd, &h_dcrow0, &d_dcrow0))
         return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    int32_t *h_cur, *d_cur, *h_off, *d_off;             // per-step copies of the four index slices; running offset
+    if (!st.take(4 * p.B, &h_cur, &d_cur) || !st.take(1, &h_off, &d_off)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    h_off[0] = 0;
     std::vector<std::pair<int64_t, int>> steps;        // (offset into the arrays, rows) per step
     {
         int64_t r = 0;
@@ -868,22 +881,62 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
             launch_scatter_i32(c->argmax, out_argmax, d_src, np, s);
         }
     }
-    for (auto& stp : steps) {
-        const int64_t o = stp.first;
-        const int rows = stp.second;
-        launch_embed(c->embed, m.dtype, tokens, d_dsrc + o, c->resid, nullptr, nullptr, rows, m.d_model, m.vocab, s);
+    // ---- decode steps.  Every step first copies its slice of the index arrays into fixed per-step buffers (and
+    // advances a device-side offset), so all its launches have the same arguments as those of any other step with
+    // the same number of live sequences: such a step is captured once as a graph and replayed, which removes the
+    // ~260 host launches per step that otherwise bound the loop.
+    auto run_step = [&](int rows) {
+        launch_step_prologue(d_dsrc, d_dpos, d_dcrow, d_dcrow0, d_cur, d_off, rows, (int)p.B, s);
+        const int32_t *cur_src = d_cur, *cur_pos = d_cur + p.B, *cur_crow = d_cur + 2 * p.B, *cur_crow0 = d_cur + 3 * p.B;
+        launch_embed(c->embed, m.dtype, tokens, cur_src, c->resid, nullptr, nullptr, rows, m.d_model, m.vocab, s);
         for (int l = 0; l < m.n_layers; ++l) {
-            block_decode(c, l, rows, d_dpos + o, d_dcrow + o, d_dcrow0 + o);
-            emit(l, rows, d_dsrc + o);
+            block_decode(c, l, rows, cur_pos, cur_crow, cur_crow0);
+            emit(l, rows, cur_src);
         }
         if (out_argmax) {
             lm_head_logits(c, rows);
             launch_argmax(c->logits, rows, m.vocab, nullptr, 0.f, c->argmax, nullptr, nullptr, s);
-            launch_scatter_i32(c->argmax, out_argmax, d_dsrc + o, rows, s);
+            launch_scatter_i32(c->argmax, out_argmax, cur_src, rows, s);
+        }
+    };
+    std::vector<int> steps_with(p.B + 1, 0);
+    for (auto& stp : steps) ++steps_with[stp.second];
+    std::vector<hipGraphExec_t> execs(p.B + 1, nullptr);
+    std::vector<hipGraph_t> graphs(p.B + 1, nullptr);
+    auto drop_graphs = [&]() {
+        for (auto& e : execs) if (e) { (void)hipGraphExecDestroy(e); e = nullptr; }
+        for (auto& g : graphs) if (g) { (void)hipGraphDestroy(g); g = nullptr; }
+    };
+    constexpr int GRAPH_MIN_STEPS = 4;                          // below this an instantiation costs more than it saves
+    for (auto& stp : steps) {
+        const int rows = stp.second;
+        if (steps_with[rows] < GRAPH_MIN_STEPS) { run_step(rows); continue; }
+        if (!execs[rows]) {
+            hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+            if (e == hipSuccess) {
+                c->capturing = true;
+                run_step(rows);
+                c->capturing = false;
+                e = hipStreamEndCapture(s, &graphs[rows]);
+            }
+            if (e == hipSuccess) e = hipGraphInstantiate(&execs[rows], graphs[rows], nullptr, nullptr, 0);
+            if (e != hipSuccess) {
+                drop_graphs();
+                return c->fail(VL_E_HIP, fmt("capturing a decode step as a graph failed: %s", hipGetErrorString(e)));
+            }
+        }
+        const hipError_t e = hipGraphLaunch(execs[rows], s);
+        if (e != hipSuccess) {
+            drop_graphs();
+            return c->fail(VL_E_HIP, fmt("hipGraphLaunch failed: %s", hipGetErrorString(e)));
         }
     }
-    HIP_TRY(c, hipGetLastError());
-    HIP_TRY(c, hipStreamSynchronize(s));
+    {
+        const hipError_t e1 = hipGetLastError(), e2 = hipStreamSynchronize(s);
+        drop_graphs();
+        if (e1 != hipSuccess || e2 != hipSuccess)
+            return c->fail(VL_E_HIP, fmt("decode steps failed: %s", hipGetErrorString(e1 != hipSuccess ? e1 : e2)));
+    }
     return VL_OK;
 }
 

@@ -35,6 +35,9 @@ void launch_load_hidden(const void* in, int dtype, float* resid, int64_t rows, i
 // out[(dst ? dst[n] : n), :] = resid[n, :] converted to `dtype`.
 void launch_store_hidden(const float* resid, void* out, int dtype, const int32_t* dst, int64_t rows, int d,
                          hipStream_t s);
+// Token-by-token path: copy rows [*off, *off + rows) of four index arrays into cur[k * stride + i], then *off += rows.
+void launch_step_prologue(const int32_t* a0, const int32_t* a1, const int32_t* a2, const int32_t* a3, int32_t* cur, int32_t* off,
+                          int rows, int stride, hipStream_t s);
 void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, int64_t rows, hipStream_t s);
 void launch_fill_u8(uint8_t* p, uint8_t v, int64_t n, hipStream_t s);
 

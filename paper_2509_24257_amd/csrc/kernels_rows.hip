@@ -268,6 +268,29 @@ void launch_load_hidden(const void* in, int dtype, float* resid, int64_t rows, i
         load_hidden_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((const float*)in, resid, d);
 }
 
+// ---------------------------------------------------------------- per-step index slices of the token-by-token path
+// cur[k * stride + i] = array_k[off + i] for the four index arrays, then off += rows.  One workgroup; every lane reads
+// the offset before lane 0 advances it.
+__global__ __launch_bounds__(256) void step_prologue_kernel(const int32_t* __restrict__ a0, const int32_t* __restrict__ a1,
+                                                            const int32_t* __restrict__ a2, const int32_t* __restrict__ a3,
+                                                            int32_t* __restrict__ cur, int32_t* __restrict__ off, int rows,
+                                                            int stride) {
+    const int o = *off;
+    __syncthreads();
+    for (int i = threadIdx.x; i < rows; i += 256) {
+        cur[i] = a0[o + i];
+        cur[stride + i] = a1[o + i];
+        cur[2 * stride + i] = a2[o + i];
+        cur[3 * stride + i] = a3[o + i];
+    }
+    if (threadIdx.x == 0) *off = o + rows;
+}
+
+void launch_step_prologue(const int32_t* a0, const int32_t* a1, const int32_t* a2, const int32_t* a3, int32_t* cur, int32_t* off,
+                          int rows, int stride, hipStream_t s) {
+    step_prologue_kernel<<<1, 256, 0, s>>>(a0, a1, a2, a3, cur, off, rows, stride);
+}
+
 __global__ void scatter_i32_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ out,
                                    const int32_t* __restrict__ dst, int64_t rows) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -205,6 +205,13 @@ def test_small_bf16_decode_commit_both_forms(small_bf16):
     say("small bf16 verify of the decode commitments")
     flags, _, sm = H.run_verify(ctx, wl, x, st_p, amax_p)
     assert flags.all() and sm["n_rejected"] == 0
+    say("small bf16 decode_commit again after other work: the replayed step graphs give the same bits")
+    for _ in range(2):
+        _, st_again, amax_again = H.run_commit(ctx, wl, x, "decode", prompt_lens=wl.prompt_lens)
+        assert st_again.tobytes() == st_p.tobytes() and amax_again.tobytes() == amax_p.tobytes()
+        H.run_commit(ctx, wl, x, "prefill")
+    _, st_again, _ = H.run_commit(ctx, wl, x, "decode", prompt_lens=None)
+    assert st_again.tobytes() == st_d.tobytes()
 
 
 def test_small_bf16_results_are_bit_reproducible_and_batch_independent(small_bf16):
