@@ -72,8 +72,8 @@ def sampled_check(ctx, wl, seq, prefix, extra_tamper=3):
         r = H.rel_l2_rows(val[ci][rows], hid[l])
         rf = H.rel_l2_rows(hidr[l], hid[l])
         rg = H.rel_l2_rows(val[ci][rows], hidr[l])
-        print(f"  layer {l}: rel-L2 gpu-vs-exact mean {r.mean():.2e} max {r.max():.2e} | bf16-model-vs-exact mean {rf.mean():.2e} "
-              f"| gpu-vs-bf16-model mean {rg.mean():.2e} max {rg.max():.2e}", flush=True)
+        H.progress(f"  layer {l}: rel-L2 gpu-vs-exact mean {r.mean():.2e} max {r.max():.2e} | bf16-model-vs-exact mean {rf.mean():.2e} "
+                   f"| gpu-vs-bf16-model mean {rg.mean():.2e} max {rg.max():.2e}")
         assert r.mean() <= 1.15 * rf.mean() + 1e-3
         assert r.max() <= 1.25e-2 * math.sqrt(l)
         assert rg.max() <= 0.75e-2 * math.sqrt(l)
@@ -81,8 +81,8 @@ def sampled_check(ctx, wl, seq, prefix, extra_tamper=3):
     gap_top2 = srt[:, -1] - srt[:, -2]
     zg_full = H.get_logits(ctx, lo, lo + prefix, m.vocab)
     err, err_fmt = np.abs(zg_full - z).max(), np.abs(zr - z).max()
-    print(f"  logits max-abs err: gpu-vs-exact {err:.3e}, bf16-model-vs-exact {err_fmt:.3e}, gpu-vs-bf16-model "
-          f"{np.abs(zg_full - zr).max():.3e}", flush=True)
+    H.progress(f"  logits max-abs err: gpu-vs-exact {err:.3e}, bf16-model-vs-exact {err_fmt:.3e}, gpu-vs-bf16-model "
+               f"{np.abs(zg_full - zr).max():.3e}")
     assert err <= 1.25 * err_fmt + 0.02 and err <= 0.6
     # the argmax kernel itself is exact: it must reproduce the argmax of the logits it was given, over the full vocabulary
     np.testing.assert_array_equal(amax[rows], np.argmax(zg_full, axis=1))
@@ -93,7 +93,7 @@ def sampled_check(ctx, wl, seq, prefix, extra_tamper=3):
     np.testing.assert_array_equal(amax[rows][clear], O.argmax_lowest(z)[clear])
     loose = gap_top2 >= 0.1
     agree = float((amax[rows][loose] == O.argmax_lowest(z)[loose]).mean()) if loose.any() else 1.0
-    print(f"  argmax agreement where the oracle's top-2 gap >= 0.1: {agree:.4f} ({loose.sum()} positions)", flush=True)
+    H.progress(f"  argmax agreement where the oracle's top-2 gap >= 0.1: {agree:.4f} ({loose.sum()} positions)")
     assert agree >= 0.9
 
     # ---- commitments: oracle states on the sampled rows, the library's own states elsewhere; tamper both
@@ -115,7 +115,7 @@ def sampled_check(ctx, wl, seq, prefix, extra_tamper=3):
 
     say(f"{wl.name}: GPU vl_verify_prefill")
     flags, stats, sm = H.run_verify(ctx, wl, x, com_st, cam_t if wl.check_argmax else None)
-    print(f"  verify: {sm['ms_forward']:.1f} ms, compare part {sm['ms_compare']:.2f} ms, rejected {sm['n_rejected']}", flush=True)
+    H.progress(f"  verify: {sm['ms_forward']:.1f} ms, compare part {sm['ms_compare']:.2f} ms, rejected {sm['n_rejected']}")
     expect = np.ones(n, np.uint8)
     expect[pos] = 0
     np.testing.assert_array_equal(flags, expect)                          # all N positions against the planted mask
@@ -165,7 +165,7 @@ def test_workload1_decode_commitments_verify_clean(ctx_8b):
     val_p, _, amax_p = H.run_commit(ctx_8b, wl, x, "prefill")
     for ci, l in enumerate(wl.commit_layers):
         r = H.rel_l2_rows(val_d[ci], val_p[ci])
-        print(f"  layer {l}: honest decode-vs-prefill rel-L2 max {r.max():.2e}", flush=True)
+        H.progress(f"  layer {l}: honest decode-vs-prefill rel-L2 max {r.max():.2e}")
         assert r.max() <= wl.tol_rel_l2 / 2
     pos = synth.tamper_positions(wl)
     com_t = synth.tamper_hidden(wl, val_d, pos)
@@ -185,7 +185,7 @@ def test_workload1_decode_commitments_verify_clean(ctx_8b):
                                           st_t[ci][None], cam_t if last else None)
         np.testing.assert_array_equal(f, expect)
         honest = expect.astype(bool)
-        print(f"  segment ({lo},{hi}]: honest rel-L2 max {stt[0]['rel_l2'][honest].max():.2e}, {sm['ms_forward']:.1f} ms", flush=True)
+        H.progress(f"  segment ({lo},{hi}]: honest rel-L2 max {stt[0]['rel_l2'][honest].max():.2e}, {sm['ms_forward']:.1f} ms")
         assert stt[0]["rel_l2"][honest].max() <= wl.tol_rel_l2 / 2
 
     say("workload 1: segment (8,16] against the oracle's segment verifier on the first 64 rows of sequence 2")
@@ -205,7 +205,7 @@ def test_workload1_decode_commitments_verify_clean(ctx_8b):
     # which for 8 blocks from a common start is bounded as in sampled_check
     d_exact = np.abs(stt[0]["rel_l2"][rows] - ref_stats[None]["stats"][0]["rel_l2"]).max()
     d_fmt = np.abs(stt[0]["rel_l2"][rows] - ref_stats["bf16"]["stats"][0]["rel_l2"]).max()
-    print(f"  rel-L2 statistic vs oracle: exact-arithmetic model {d_exact:.2e}, bf16-operand model {d_fmt:.2e}", flush=True)
+    H.progress(f"  rel-L2 statistic vs oracle: exact-arithmetic model {d_exact:.2e}, bf16-operand model {d_fmt:.2e}")
     assert d_exact <= 1.25e-2 * math.sqrt(8) and d_fmt <= 0.75e-2 * math.sqrt(8)
 
     say("workload 1: Merkle roots of all 4 x 8192 committed states; sampled rows and openings against the oracle")
@@ -216,7 +216,7 @@ def test_workload1_decode_commitments_verify_clean(ctx_8b):
     ctx_8b.vl_op_merkle_roots(d_st.data_ptr(), P.VL_BF16, c_n, d_roots.data_ptr())
     dt = time.time() - t0
     roots = d_roots.cpu().numpy()
-    print(f"  {c_n} roots over {wl.model.d_model} scalars each in {dt * 1e3:.1f} ms = {dt / (c_n * wl.model.d_model) * 1e9:.3f} ns per scalar", flush=True)
+    H.progress(f"  {c_n} roots over {wl.model.d_model} scalars each in {dt * 1e3:.1f} ms = {dt / (c_n * wl.model.d_model) * 1e9:.3f} ns per scalar")
     flat = st_t.reshape(c_n, wl.model.d_model)
     sample = np.random.default_rng(7).choice(c_n, 10, replace=False)
     for r in sample:
@@ -271,7 +271,7 @@ def test_long_context_attention_sampled_rows(ctx_8b):
         g = j // (hq // hkv)
         ref = O.causal_attention(q[:, j:j + 1], k[:, g:g + 1], v[:, g:g + 1], qrows)
         err = np.abs(got[qrows][:, j] - ref[:, 0]).max()
-        print(f"  head {j}: max-abs err {err:.3e}", flush=True)
+        H.progress(f"  head {j}: max-abs err {err:.3e}")
         assert err <= 2e-2
 
 
