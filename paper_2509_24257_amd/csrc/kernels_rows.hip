@@ -81,13 +81,54 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_kernel(const float* __res
     }
 }
 
+// One wave per row, the row held in registers between the sum of squares and the scaling (read once): d = 256 * NV.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_wave_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                           T* __restrict__ out, int64_t rows, float eps, bool out_tiled) {
+    constexpr int D = 256 * NV;
+    const int lane = threadIdx.x & 63;
+    const int64_t n = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= rows) return;                                      // whole wave leaves together; no barrier below
+    const float4* xr = (const float4*)(x + n * (int64_t)D);
+    float4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = xr[lane + WAVE * i];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    ss = wave_sum(ss);
+    const float r = 1.0f / sqrtf(ss / (float)D + eps);
+    const float4* g4 = (const float4*)gain;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int q = lane + WAVE * i;
+        const float4 g = g4[q];
+        T* o = out + (out_tiled ? tiled_off(n, 4 * q, D) : n * (int64_t)D + 4 * q);
+        store4(o, v[i].x * r * g.x, v[i].y * r * g.y, v[i].z * r * g.z, v[i].w * r * g.w);
+    }
+}
+
+template <typename T>
+static void launch_rmsnorm_t(const float* x, const float* gain, T* out, int64_t rows, int d, float eps, hipStream_t s, bool tiled) {
+    const dim3 grid((unsigned)((rows + 3) / 4));
+#define VL_RMS(NV) rmsnorm_wave_kernel<T, NV><<<grid, 256, 0, s>>>(x, gain, out, rows, eps, tiled)
+    switch ((d & 255) ? 0 : d >> 8) {
+        case 1: VL_RMS(1); break;
+        case 2: VL_RMS(2); break;
+        case 4: VL_RMS(4); break;
+        case 8: VL_RMS(8); break;
+        case 16: VL_RMS(16); break;
+        case 32: VL_RMS(32); break;
+        default: rmsnorm_kernel<T><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, out, d, eps, tiled); break;
+    }
+#undef VL_RMS
+}
+
 void launch_rmsnorm(const float* x, const float* gain, void* out, int dtype, int64_t rows, int d, float eps,
                     hipStream_t s, bool out_tiled) {
     if (rows <= 0) return;
-    if (dtype == VL_BF16)
-        rmsnorm_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (bf16*)out, d, eps, out_tiled);
-    else
-        rmsnorm_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>(x, gain, (float*)out, d, eps, false);
+    if (dtype == VL_BF16) launch_rmsnorm_t<bf16>(x, gain, (bf16*)out, rows, d, eps, s, out_tiled);
+    else launch_rmsnorm_t<float>(x, gain, (float*)out, rows, d, eps, s, false);
 }
 
 // ---------------------------------------------------------------- row-major -> tiled image (weights, at load time)
