@@ -37,7 +37,15 @@ def toks(n, vocab, seed=0):
     return np.random.default_rng(seed).integers(0, vocab, size=n).astype(np.int32)
 
 
-@pytest.mark.parametrize("cfg", [TINY, TINY_BF], ids=["f32", "bf16-weights"])
+# one block at the real 8B evaluation shape (32 / 8 heads of 128, d = 4096, F = 14336, base 500000, bf16 weight values):
+# pins whatever depends on the shape itself, e.g. the mapping of 4 query heads onto each KV head
+BLOCK_8B = synth.ModelCfg("8b-block", 1, 4096, 32, 8, 128, 14336, 512, 1e-5, 500000.0, "bf16", 0.02, seed=1002)
+# the head geometry of the 70B shape (64 / 8 heads of 128, d = 8192) with a narrow feed-forward to keep the test light
+HEADS_70B = synth.ModelCfg("70b-heads", 1, 8192, 64, 8, 128, 2048, 512, 1e-5, 500000.0, "bf16", 0.01, seed=1004)
+
+
+@pytest.mark.parametrize("cfg", [TINY, TINY_BF, BLOCK_8B, HEADS_70B],
+                         ids=["f32", "bf16-weights", "8b-shape-block", "70b-head-geometry"])
 def test_forward_matches_transformers_llama(cfg):
     transformers = pytest.importorskip("transformers")
     hc = transformers.LlamaConfig(
@@ -52,7 +60,7 @@ def test_forward_matches_transformers_llama(cfg):
     sd = {}
     for l in range(cfg.n_layers):
         for k, nm in names.items():
-            sd[f"model.layers.{l}.{nm}.weight"] = torch.from_numpy(synth.weight_values_f32(cfg, k, l, 1)).double()
+            sd[f"model.layers.{l}.{nm}.weight"] = torch.from_numpy(synth.weight_values_f32(cfg, k, l, 8)).double()
     sd["model.embed_tokens.weight"] = torch.from_numpy(synth.weight_values_f32(cfg, O.EMBED, 0, 1)).double()
     sd["model.norm.weight"] = torch.from_numpy(synth.weight_values_f32(cfg, O.FINAL_NORM, 0, 1)).double()
     sd["lm_head.weight"] = torch.from_numpy(synth.weight_values_f32(cfg, O.LM_HEAD, 0, 1)).double()
