@@ -42,8 +42,8 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
     constexpr int LPK = HD / 8;                                 // lanes per key row
     constexpr int KPP = WAVE / LPK;                             // keys per pass
     constexpr int DPL = HD / WAVE;                              // value channels per lane
-    constexpr int KCH = (G >= 4 && LPK > 8) ? 8 : LPK;          // key passes requested together
-    constexpr int VCH = G >= 8 ? 16 : 32;                       // value rows requested together
+    constexpr int KCH = (G >= 8 && LPK > 8) ? 8 : LPK;          // key passes requested together
+    constexpr int VCH = G >= 8 ? 16 : (G >= 4 ? 32 : 64);       // value rows requested together
     __shared__ float part_o[AD_WAVES][G][HD];
     __shared__ float part_m[AD_WAVES][G], part_l[AD_WAVES][G];
     const int64_t row = blockIdx.x;
