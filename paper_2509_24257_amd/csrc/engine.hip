@@ -90,7 +90,7 @@ Plan make_plan(const vl_model_cfg& c) {
     // values transposed for the matrix-core attention: every sequence starts on a multiple of 8 columns, plus one
     // key tile of slack so that the last tile of the last sequence can be read whole
     p.vt_ld = align_up(p.N + 8 * p.B + 64, 64);
-    p.max_tiles = p.N / 128 + p.B + 1;
+    p.max_tiles = p.N / 64 + p.B + 1;
     p.stage_ints = 12 * p.N + 6 * p.max_tiles + 8 * p.B + 64;
     int64_t w = 0;
     w += align_up(p.N * p.d * 4, ALIGN);                 // residual stream (fp32)
@@ -270,8 +270,10 @@ struct Stage {
     }
 };
 
-// Builds pos / seq_row0 / vt_col / tiles for sequences of the given lengths packed back to back.
-bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, bool want_tiles, BatchIdx* dev) {
+// Builds pos / seq_row0 / vt_col / tiles (one per q_span queries; none if q_span = 0) for sequences of the given
+// lengths packed back to back.
+bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, int q_span, BatchIdx* dev) {
+    const bool want_tiles = q_span > 0;
     int64_t n = 0;
     for (int32_t t : lens) n += t;
     int32_t *hp, *hs, *hv;
@@ -285,8 +287,8 @@ bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, bool want_tile
             hv[row + i] = (int32_t)(col + i);
         }
         if (want_tiles)
-            for (int32_t q0 = 0; q0 < t; q0 += 128) {
-                const int32_t qr = std::min(128, t - q0);
+            for (int32_t q0 = 0; q0 < t; q0 += q_span) {
+                const int32_t qr = std::min(q_span, t - q0);
                 tiles.push_back({(int32_t)(row + q0), qr, (int32_t)row, q0 + qr, (int32_t)col, q0});
             }
         row += t;
@@ -304,6 +306,9 @@ bool build_batch_idx(Stage& st, const std::vector<int32_t>& lens, bool want_tile
     }
     return true;
 }
+
+// Queries per attention tile of this model's prefill (0: the fp32 path builds no tiles).
+int attn_span(const vl_ctx* c) { return c->bf16 ? attn_mfma_q_span(c->cfg.n_q_heads, c->cfg.n_kv_heads) : 0; }
 
 // bf16 models: every GEMM runs on the matrix cores; up to 64 rows (a decode step) take the weight-streaming kernel,
 // more rows the 256 x 256 tile kernel.  fp32 models: vector-ALU GEMM.
@@ -449,7 +454,7 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
     Stage st(c->h_idx, c->d_idx, c->plan.stage_ints);
     BatchIdx bi;
     std::vector<int32_t> lens(lengths, lengths + B);
-    if (!build_batch_idx(st, lens, c->bf16, &bi)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    if (!build_batch_idx(st, lens, attn_span(c), &bi)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
     rc = upload_stage(c, st);
     if (rc) return rc;
 
@@ -824,7 +829,7 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
     Stage st(c->h_idx, c->d_idx, p.stage_ints);
     // ---- prompt part: one prefill over the packed prompts, filling the KV cache
     BatchIdx bi;
-    if (!build_batch_idx(st, plen, c->bf16, &bi)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    if (!build_batch_idx(st, plen, attn_span(c), &bi)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
     const int64_t np = bi.rows;
     int32_t *h_src, *d_src, *h_crow, *d_crow;
     if (!st.take(np, &h_src, &d_src) || !st.take(np, &h_crow, &d_crow)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
@@ -1022,7 +1027,7 @@ int vl_op_attention_bf16(vl_ctx* c, const void* qkv, const int32_t* lengths, int
     Stage st(c->h_idx, c->d_idx, c->plan.stage_ints);
     BatchIdx bi;
     std::vector<int32_t> lens(lengths, lengths + B);
-    if (!build_batch_idx(st, lens, true, &bi)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
+    if (!build_batch_idx(st, lens, attn_mfma_q_span(c->cfg.n_q_heads, c->cfg.n_kv_heads), &bi)) return c->fail(VL_E_CAPACITY, "index staging buffer too small");
     int rc = upload_stage(c, st);
     if (rc) return rc;
     launch_transpose_v(qkv, c->vt, bi.vt_col, n, m.n_q_heads, m.n_kv_heads, m.head_dim, c->plan.vt_ld, c->stream);

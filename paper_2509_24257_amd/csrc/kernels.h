@@ -81,10 +81,12 @@ void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const vo
 // Causal GQA flash attention on the matrix cores over packed sequences.
 //   qkv bf16 [N][(hq+2hkv)*hd], vt bf16 [hkv][hd][ldv] (values transposed, column = vt column of the token),
 //   tiles: host-built work list (see engine), out bf16 [N][hq*hd].
-struct AttnTile { int32_t q_row0, q_rows, kv_row0, kv_len, vt_col0, pos0; };  // one 128-query tile of a sequence:
-//   q_row0  packed row of its first query, q_rows valid queries (<= 128), pos0 position of the first query,
-//   kv_row0 packed row of the sequence's first token, kv_len = pos0 + q_rows keys are visible to the tile,
-//   vt_col0 column of the sequence's first token in vt (a multiple of 8)
+struct AttnTile { int32_t q_row0, q_rows, kv_row0, kv_len, vt_col0, pos0; };  // one query tile of a sequence:
+//   q_row0  packed row of its first query, q_rows valid queries (<= attn_mfma_q_span), pos0 position of the first query
+//           (a multiple of the span), kv_row0 packed row of the sequence's first token, kv_len = pos0 + q_rows keys are
+//   visible to the tile, vt_col0 column of the sequence's first token in vt (a multiple of 8)
+// Queries per tile for this head geometry: 64, 128 or 256 (a workgroup serves 4, 2 or 1 query heads of one KV head).
+int attn_mfma_q_span(int hq, int hkv);
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
                       void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled = false);
 

@@ -1,208 +1,387 @@
 // Causal grouped-query flash attention for the bf16 prefill, on the gfx950 matrix cores.
 //
-// One workgroup (4 waves) handles 128 consecutive queries of one sequence for one query head; each wave owns
-// 32 queries.  Keys are walked 64 at a time; the K tile [64 keys][hd] and the transposed V tile [hd][64 keys]
-// are staged in LDS (rows padded by 16 bytes so that the MFMA operand reads of consecutive rows hit
-// different banks).  Everything is computed TRANSPOSED so that one lane always owns one query:
+// One workgroup = 4 waves, one per SIMD, each with up to 512 registers.  A wave owns 64 queries of one query head
+// (two MFMA column blocks of 32), so every key / value fragment it reads from LDS feeds two MFMAs.  The four waves of
+// a workgroup always share one KV head and therefore one stream of key / value tiles:
+//   HPW = 4 : four query heads of the group x the same 64 queries          (Hq / Hkv a multiple of 4)
+//   HPW = 2 : two query heads x two consecutive 64-query sub-tiles          (Hq / Hkv even)
+//   HPW = 1 : one query head x four consecutive 64-query sub-tiles          (otherwise)
 //
+// Everything is computed TRANSPOSED so that one lane always owns one query:
 //   S^T[key][q] = K * Q^T      A operand = K rows from LDS, B operand = Q rows held in registers
 //   O^T[c][q]  += V^T * P^T    A operand = V^T rows from LDS, B operand = P^T straight from the S^T registers
-//
 // With the 32x32x16 MFMA the result lane l holds column (l % 32) = the query, and its 16 registers hold rows
-// 8*(r/4) + 4*(l/32) + r%4 = keys (or channels).  The running max / sum / rescale of the online softmax are
-// therefore per-lane scalars, and the row reductions are over a lane's own registers plus one exchange with
-// lane l^32.  The probabilities feed the second MFMA without leaving registers: the k index of that MFMA is
-// a dummy (contraction) index, so any assignment of keys to (register, lane half) is valid as long as the
-// V^T operand is gathered with the same assignment - two 8-byte LDS reads per operand.
+// 8*(r/4) + 4*(l/32) + r%4.  The K fragment puts key perm(i) on row i, perm swapping bits 2 and 3 of i; register r
+// of lane half h then holds key 16*(r/8) + 8*h + r%8 of the 32-key block, so registers 8*s2 .. 8*s2+7 are eight
+// CONSECUTIVE keys - exactly one 16-byte read of a V^T row for the second MFMA, whose contraction index they become.
 //
-// Softmax statistics and all accumulators are fp32; probabilities are rounded to bf16 for the second MFMA.
+// Keys are walked in blocks of 32 inside tiles of 64.  Tiles travel global -> LDS directly (global_load_lds, 16 bytes
+// per lane) into a ring of four slots; the 16-byte chunks of a row are XOR-swizzled on the global-address side so the
+// fragment reads are free of bank conflicts.  One barrier per tile.
+//
+// Software pipeline over blocks j: while the vector ALUs turn S_j into probabilities P_j, the matrix pipe computes
+// S_{j+1} and O += V_{j-1} P_{j-1}.  No MFMA of a step depends on a vector result of the same step.
+//
+// Softmax: statistics and accumulators are fp32, probabilities are rounded to bf16 for the second MFMA.  The exponent
+// reference m of a query is moved only when a score outgrows it by more than FA_SLACK (base-2 units): any reference
+// gives the same quotient O / l, a stale one merely bounds the probabilities by 2^FA_SLACK instead of 1, and O is
+// rescaled on a rare wave-uniform side path instead of on every block.  On the usual path a lane never needs the
+// other lane half.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
 namespace vl {
 
-constexpr int FA_BQ = 128;        // queries per workgroup
-constexpr int FA_BK = 64;         // keys per step
+constexpr int FA_BK = 64;         // keys per tile (two blocks of 32)
+constexpr int FA_QW = 64;         // queries per wave
 constexpr int FA_THREADS = 256;
+constexpr int FA_SLOTS = 4;
+constexpr float FA_SLACK = 8.0f;  // how far (base 2) a score may outgrow the exponent reference before O is rescaled
 
-template <int HD>
-__global__ __launch_bounds__(FA_THREADS, 2) void attn_mfma_kernel(const bf16* __restrict__ qkv, int64_t n_rows,
+#define FA_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+constexpr int FA_WAIT_VM = 0x0F70;      // s_waitcnt vmcnt(0), other counters untouched (gfx9 encoding)
+
+int attn_mfma_heads_per_wg(int hq, int hkv) {
+    const int g = hq / hkv;
+    return g % 4 == 0 ? 4 : (g % 2 == 0 ? 2 : 1);
+}
+int attn_mfma_q_span(int hq, int hkv) { return FA_QW * 4 / attn_mfma_heads_per_wg(hq, hkv); }
+
+template <int HD, int HPW>
+__global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __restrict__ qkv, int64_t n_rows,
                                                                const bf16* __restrict__ vt, int64_t ldv,
                                                                const AttnTile* __restrict__ tiles,
                                                                bf16* __restrict__ out, int hq, int hkv, float scale_log2e,
                                                                bool out_tiled) {
-    constexpr int KP = HD + 8;               // K tile row pitch (elements)
-    constexpr int VP = FA_BK + 8;            // V^T tile row pitch
-    constexpr int KSTEPS = HD / 16;          // MFMA k-steps over the head dimension
-    constexpr int DB = HD / 32;              // 32-channel output blocks
-    __shared__ __align__(16) bf16 ks[FA_BK * KP];
-    __shared__ __align__(16) bf16 vs[HD * VP];
+#if defined(__HIP_DEVICE_COMPILE__)     // the host pass needs the launch stub only; the body uses device-only types
+    constexpr int KSTEPS = HD / 16;               // MFMA k-steps over the head dimension
+    constexpr int DB = HD / 32;                   // 32-channel output blocks
+    constexpr int KROW = HD * 2;                  // bytes per key row in LDS
+    constexpr int KCPR = HD / 8;                  // 16-byte chunks per key row (16 or 8)
+    constexpr int K_BYTES = FA_BK * KROW;         // K tile
+    constexpr int V_BYTES = HD * FA_BK * 2;       // V^T tile: HD rows of 64 keys (128 bytes)
+    constexpr int SLOT = K_BYTES + V_BYTES;
+    constexpr int K_RPI = 1024 / KROW;            // key rows filled by one 1 KB load instruction
+    constexpr int NI_K = FA_BK / K_RPI / 4;       // load instructions per wave and tile, K
+    constexpr int NI_V = HD / 8 / 4;              //                                      V^T (8 rows per instruction)
+    __shared__ __align__(1024) unsigned char ring[FA_SLOTS * SLOT];
 
-    const AttnTile t = tiles[blockIdx.x];
-    const int head = blockIdx.y, g = head / (hq / hkv);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Workgroup ids are dealt round-robin to the 8 XCDs.  id = tile * n_groups + x with x -> (KV head x % hkv, head
+    // group x / hkv inside it): when hkv is a multiple of 8 every XCD keeps meeting the same KV heads, whose keys and
+    // values then stay in that XCD's L2 while the query tiles (longest first) walk over them.
+    const int n_groups = hq / HPW;
+    const int gx = blockIdx.x % n_groups;
+    const AttnTile t = tiles[blockIdx.x / n_groups];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lq = lane & 31, half = lane >> 5;
+    const int g = gx % hkv;                       // KV head
+    const int head = g * (hq / hkv) + (gx / hkv) * HPW + wave % HPW;
+    const int qs = wave / HPW;                    // 64-query sub-tile of this wave
     const int64_t pitch = (int64_t)(hq + 2 * hkv) * HD;
 
-    // ---- this lane's query row (clamped into the tile; rows past q_rows are computed and dropped)
-    const int q_local = wave * 32 + lq;
-    const int q_idx = min(q_local, t.q_rows - 1);
-    const int q_pos = t.pos0 + q_idx;
-    const bf16* qp = qkv + (int64_t)(t.q_row0 + q_idx) * pitch + (int64_t)head * HD + half * 8;
-    bf16x8 qf[KSTEPS];
+    // ---- this lane's two queries (clamped into the tile; rows past q_rows are computed and dropped)
+    int q_pos[2];
+    bf16x8 qf[2][KSTEPS];
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) qf[s] = *(const bf16x8*)(qp + s * 16);
+    for (int qb = 0; qb < 2; ++qb) {
+        const int q_idx = min(qs * FA_QW + qb * 32 + lq, t.q_rows - 1);
+        q_pos[qb] = t.pos0 + q_idx;
+        const bf16* qp = qkv + (int64_t)(t.q_row0 + q_idx) * pitch + (int64_t)head * HD + half * 8;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) qf[qb][s] = *(const bf16x8*)(qp + s * 16);
+    }
+    const int wave_first_pos = t.pos0 + qs * FA_QW;
 
-    f32x16 o[DB];
+    // ---- tile loads: lane -> (row, physical chunk) of the 1 KB piece its wave fills; the global side applies the swizzle.
+    // Buffer loads (base in scalar registers, 32-bit lane offsets) straight into LDS.
+    const int n_tiles = (t.kv_len + FA_BK - 1) / FA_BK;
+    const bf16* kseq = qkv + (int64_t)t.kv_row0 * pitch + (int64_t)hq * HD + (int64_t)g * HD;
+    const bf16* vseq = vt + (int64_t)g * HD * ldv + t.vt_col0;
+    const int k_last = (int)(n_rows - 1 - t.kv_row0);                 // rows past the buffer re-read its last row (masked)
+    const uint32_t k_bytes = (uint32_t)min((int64_t)(k_last + 1) * pitch * 2 - (int64_t)(hq + g) * HD * 2, (int64_t)0xFFFFFFFFll);
+    const uint32_t v_bytes = (uint32_t)(((int64_t)HD * ldv - t.vt_col0) * 2);
+    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kseq, 0, k_bytes, 0x00020000);
+    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vseq, 0, v_bytes, 0x00020000);
+    const int k_row = wave * K_RPI + lane / KCPR;                     // + 4 * K_RPI * i
+    const int k_swz = KCPR == 16 ? (k_row & 15) : ((k_row >> 1) & 7);
+    const uint32_t k_col = ((lane % KCPR) ^ k_swz) * 16;              // bytes
+    const uint32_t row_bytes = (uint32_t)pitch * 2;
+    const int v_row = wave * 8 + (lane >> 3);                         // + 32 * i
+    uint32_t v_lane[NI_V];
+#pragma unroll
+    for (int i = 0; i < NI_V; ++i) v_lane[i] = (uint32_t)(v_row + 32 * i) * (uint32_t)ldv * 2 + ((lane & 7) ^ ((v_row >> 1) & 7)) * 16;
+    auto issue_tile = [&](int tile) {
+        unsigned char* slot = ring + (tile & (FA_SLOTS - 1)) * SLOT + wave * 1024;
+        const int key0 = tile * FA_BK;
+#pragma unroll
+        for (int i = 0; i < NI_K; ++i) {
+            const uint32_t row = (uint32_t)min(key0 + k_row + 4 * K_RPI * i, k_last);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, FA_LDS(slot + i * 4096), 16, row * row_bytes + k_col, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < NI_V; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, FA_LDS(slot + K_BYTES + i * 4096), 16, v_lane[i] + (uint32_t)key0 * 2, 0, 0, 0);
+    };
+
+    // ---- fragment read offsets inside a slot
+    const int prow = (lq & ~12) | ((lq & 4) << 1) | ((lq & 8) >> 1);  // key row this lane feeds to the first MFMA
+    const int kx = half ^ (KCPR == 16 ? (prow & 15) : ((prow >> 1) & 7));
+    int k_off[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) k_off[s] = prow * KROW + (((2 * s) ^ kx) << 4);      // + 32 * KROW * kb
+    const int vx = half ^ ((lq >> 1) & 7);
+    int v_off[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) v_off[kb][s2] = K_BYTES + lq * 128 + (((4 * kb + 2 * s2) ^ vx) << 4);   // + 4096 * b
+
+    f32x16 o[DB][2];
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[b][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;      // l_run: this lane half's share of the row sum
-
-    const bf16* kbase = qkv + (int64_t)hq * HD + (int64_t)g * HD;
-    const bf16* vbase = vt + (int64_t)g * HD * ldv + t.vt_col0;
-    const int n_kv_tiles = (t.kv_len + FA_BK - 1) / FA_BK;
-    const int wave_first_pos = t.pos0 + wave * 32;
-
-    // The tiles travel global -> registers -> LDS; the registers of tile kt+1 are requested right after tile kt has been
-    // published in LDS, so the memory latency runs behind the arithmetic of tile kt.
-    constexpr int KLD = (FA_BK * HD / 8) / FA_THREADS, VLD = (HD * FA_BK / 8) / FA_THREADS;
-    u32x4 kreg[KLD], vreg[VLD];
-    auto fetch = [&](int key0) {
-        // K tile: 64 rows x HD, 16-byte chunks; rows past the end of the buffer re-read the last row (masked below)
+        for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) {
-            const int id = tid + FA_THREADS * i;
-            const int row = id / (HD / 8), c = id % (HD / 8);
-            const int64_t grow = min((int64_t)t.kv_row0 + key0 + row, n_rows - 1);
-            kreg[i] = *(const u32x4*)(kbase + grow * pitch + c * 8);
+            for (int r = 0; r < 16; ++r) o[b][qb][r] = 0.f;
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};                   // this lane half's share of the row sums
+
+    // One pipeline step = NSLOT matrix instructions, each followed by its share of the vector work of the step and
+    // fenced for the scheduler, so the instruction stream alternates between the two pipes exactly as written:
+    //   slots 0 .. NS-1      S_next[qb] (+)= K fragment s x Q[qb][s]                     s = slot / 2, qb = slot % 2
+    //   slots NS .. NSLOT-1  O[b][qb]    += V^T fragment (s2, b) x P_prev[qb][s2]        i = slot - NS: s2 = i / (2 DB), b = (i / 2) % DB, qb = i % 2
+    //   fragment i (K fragments first, then V^T fragments) feeds slots 2 i and 2 i + 1 and is read FA_AHEAD fragments
+    //   early into a ring of eight registers quads; the last reads of a step are the first K fragments of the NEXT
+    //   step (block 1 - KB of the tile in `nkslot`), so no step starts by waiting for LDS
+    //   vector work: slot e turns score(s) e of S_cur into probabilities; every second score closes a pair (row sum,
+    //   rounding to bf16).  The lane maxima of S_next are taken in the last slots, at least four matrix instructions
+    //   after the last one that wrote S_next.
+    constexpr int NS = 2 * KSTEPS, NSLOT = NS + 4 * DB, NFRAG = NSLOT / 2;
+    constexpr int FA_AHEAD = HD == 128 ? 5 : 4;      // <= KSTEPS: the early reads for the next step are all K fragments
+    constexpr int EPS = 32 / NSLOT;                // scores per slot (1 or 2)
+    constexpr int MAX0 = HD == 128 ? NSLOT - 8 : NSLOT - 4, MAX_PER = 16 / (NSLOT - MAX0);
+    bf16x8 fr[8];
+    auto step = [&](const unsigned char* kslot, const unsigned char* vslot, const unsigned char* nkslot, auto kb_c,
+                    const f32x16 (&Sc)[2], f32x16 (&Sn)[2], const u32x4 (&Pp)[2][2], u32x4 (&Pc)[2][2], float (&mx)[2]) {
+        constexpr int KB = decltype(kb_c)::value;
+        auto read_frag = [&](int i) {
+            if (i < KSTEPS) fr[i & 7] = *(const bf16x8*)(kslot + KB * 32 * KROW + k_off[i]);
+            else if (i < NFRAG) { const int j = i - KSTEPS; fr[i & 7] = *(const bf16x8*)(vslot + v_off[KB][j / DB] + (j % DB) * 4096); }
+            else fr[i & 7] = *(const bf16x8*)(nkslot + (1 - KB) * 32 * KROW + k_off[i - NFRAG]);
+        };
+        float pe[4] = {0.f, 0.f, 0.f, 0.f};
+        float mrun[2] = {-INFINITY, -INFINITY};
+        // closes pair u of S_cur: rounds its two probabilities to bf16 and adds them (as rounded) to the row sum
+        auto close_pair = [&](int u) {
+            const int eq = u >> 3, r0 = 2 * (u & 7);
+            const f32x2 pp = {pe[(2 * u) & 3], pe[(2 * u + 1) & 3]};
+            const bf16x2 w = __builtin_convertvector(pp, bf16x2);
+            l_run[eq] = __builtin_amdgcn_fdot2_f32_bf16(w, __builtin_bit_cast(bf16x2, 0x3F803F80u), l_run[eq], false);
+            uint32_t wi = __builtin_bit_cast(uint32_t, w);
+            asm volatile("" : "+v"(l_run[eq]), "+v"(wi));             // pinned to this slot: nothing may sink below
+            Pc[eq][r0 >> 3][(r0 & 7) >> 1] = wi;
+        };
+#pragma unroll
+        for (int slot = 0; slot < NSLOT; ++slot) {
+            const int i = slot >> 1, qb = slot & 1;
+            if (qb == 0) read_frag(i + FA_AHEAD);
+            // ---- matrix pipe
+            if (slot < NS) {
+                if (i == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(Sn[qb]) : "v"(fr[i & 7]), "a"(qf[qb][i]));
+                else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(Sn[qb]) : "v"(fr[i & 7]), "a"(qf[qb][i]));
+            } else {
+                const int j = i - KSTEPS, s2 = j / DB, b = j % DB;
+                o[b][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i & 7], __builtin_bit_cast(bf16x8, Pp[qb][s2]), o[b][qb], 0, 0, 0);
+            }
+            // ---- vector pipe: exponentials of this slot's score(s); the pair finished one slot ago is closed (its
+            // exponentials have left the transcendental unit by now)
+#pragma unroll
+            for (int k = 0; k < EPS; ++k) {
+                const int e = slot * EPS + k, eq = e >> 4, r = e & 15;
+                if ((e & 1) == 0 && e >= 2) close_pair(e / 2 - 1);
+                pe[e & 3] = __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[eq][r], scale_log2e, -m_run[eq]));
+                asm volatile("" : "+v"(pe[e & 3]));
+            }
+            if (slot >= MAX0) {
+#pragma unroll
+                for (int k = 0; k < MAX_PER; ++k) {
+                    const int op = (slot - MAX0) * MAX_PER + k, mq = op & 1, n = op >> 1;   // eight steps per query block
+                    if (n == 0) asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(mrun[mq]) : "v"(Sn[mq][0]), "v"(Sn[mq][1]), "v"(Sn[mq][2]));
+                    else if (n < 7) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(mrun[mq]) : "v"(Sn[mq][2 * n + 1]), "v"(Sn[mq][2 * n + 2]));
+                    else asm volatile("v_max_f32 %0, %0, %1" : "+v"(mrun[mq]) : "v"(Sn[mq][15]));
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // V^T tile: HD rows x 64 keys (the vt buffer is padded, so the columns always exist)
+        close_pair(15);
+        mx[0] = mrun[0];
+        mx[1] = mrun[1];
+    };
+    // S^T of the first block (nothing to overlap with yet)
+    auto first_scores = [&](const unsigned char* slot, f32x16 (&S)[2]) {
 #pragma unroll
-        for (int i = 0; i < VLD; ++i) {
-            const int id = tid + FA_THREADS * i;
-            const int row = id >> 3, c = id & 7;
-            vreg[i] = *(const u32x4*)(vbase + (int64_t)row * ldv + key0 + c * 8);
+        for (int s = 0; s < KSTEPS; ++s) {
+            const bf16x8 kf = *(const bf16x8*)(slot + k_off[s]);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                if (s == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S[qb]) : "v"(kf), "a"(qf[qb][s]));
+                else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S[qb]) : "v"(kf), "a"(qf[qb][s]));
+            }
+        }
+        // the first fragments of the first pipeline step (second block of the same tile)
+#pragma unroll
+        for (int i = 0; i < FA_AHEAD; ++i) fr[i] = *(const bf16x8*)(slot + 32 * KROW + k_off[i]);
+        // the results of these hand-issued instructions are not tracked by the compiler: let the last one drain
+        asm volatile("s_nop 15\n\ts_nop 7" : "+v"(S[0]), "+v"(S[1]));
+    };
+    // causal mask of a block that reaches past the wave's first query, and the lane maxima again
+    auto mask_block = [&](f32x16 (&S)[2], int key0, float (&mx)[2]) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int d = q_pos[qb] - key0 - 8 * half;                // key of register r = key0 + 8*half + 16*(r/8) + r%8
+            float m = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (16 * (r >> 3) + (r & 7) > d) S[qb][r] = -INFINITY;
+                m = fmaxf(m, S[qb][r]);
+            }
+            mx[qb] = m;
         }
     };
-    fetch(0);
-    const int wave_last_pos = t.pos0 + min(wave * 32 + 31, t.q_rows - 1);
-
-    for (int kt = 0; kt < n_kv_tiles; ++kt) {
-        const int key0 = kt * FA_BK;
-        __syncthreads();                                         // everyone is done with the previous tiles
+    // rare path: some query's block maximum has outgrown its reference.  The new reference is the joint maximum of
+    // both lane halves; O, l and the probabilities that have not been multiplied into O yet move with it.
+    auto move_reference = [&](const float (&mx)[2], u32x4 (&Pprev)[2][2]) {
 #pragma unroll
-        for (int i = 0; i < KLD; ++i) {
-            const int id = tid + FA_THREADS * i;
-            *(u32x4*)(ks + (id / (HD / 8)) * KP + (id % (HD / 8)) * 8) = kreg[i];
-        }
+        for (int qb = 0; qb < 2; ++qb) {
+            const float m_blk = fmaxf(mx[qb], __shfl_xor(mx[qb], 32, WAVE)) * scale_log2e;
+            const float m_new = fmaxf(m_run[qb], m_blk);              // finite: the first block holds key 0
+            const float corr = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+            m_run[qb] = m_new;
+            l_run[qb] *= corr;
+            // O lives in accumulation registers, which only these three instructions can touch; written out so that
+            // the copies stay on this path instead of being hoisted into the loop
 #pragma unroll
-        for (int i = 0; i < VLD; ++i) {
-            const int id = tid + FA_THREADS * i;
-            *(u32x4*)(vs + (id >> 3) * VP + (id & 7) * 8) = vreg[i];
-        }
-        __syncthreads();
-        if (kt + 1 < n_kv_tiles) fetch(key0 + FA_BK);
-        if (key0 > wave_last_pos) continue;                      // uniform per wave: every key of the tile is masked
-
-        // ---- S^T = K Q^T for the two 32-key blocks of this tile
-        f32x16 st[2];
+            for (int b = 0; b < DB; ++b)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) st[kb][r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                const bf16x8 kf = *(const bf16x8*)(ks + (kb * 32 + lq) * KP + s * 16 + half * 8);
-                st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], st[kb], 0, 0, 0);
-            }
-        }
-        // ---- scale (to base-2 logits), causal mask, running max
-        const bool need_mask = key0 + FA_BK - 1 > wave_first_pos;     // uniform per wave
-        float m_new = m_run;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = st[kb][r] * scale_log2e;
-                if (need_mask) {
-                    const int key = key0 + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                    if (key > q_pos) v = -INFINITY;
+                for (int r = 0; r < 16; ++r) {
+                    float x = o[b][qb][r], tmp;
+                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1"
+                                 : "+a"(x), "=&v"(tmp) : "v"(corr));
+                    o[b][qb][r] = x;
                 }
-                st[kb][r] = v;
-                m_new = fmaxf(m_new, v);
-            }
-        m_new = fmaxf(m_new, __shfl_xor(m_new, 32, WAVE));           // key 0 is visible to every query: finite
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(st[kb][r] - m_new);
-                st[kb][r] = p;
-                psum += p;
-            }
-        l_run = l_run * corr + psum;
-#pragma unroll
-        for (int b = 0; b < DB; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[b][r] *= corr;
-
-        // ---- O^T += V^T P^T.  MFMA step (kb, s2) contracts over the 16 keys held in registers 8*s2 .. 8*s2+7
-        // of both lane halves: keys kb*32 + 16*s2 + {4*half .. +3} and {8 + 4*half .. +3}.
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                bf16x8 pf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (bf16)st[kb][8 * s2 + e];
-                const int kcol = kb * 32 + s2 * 16 + half * 4;
-#pragma unroll
-                for (int b = 0; b < DB; ++b) {
-                    const bf16* vr = vs + (b * 32 + lq) * VP + kcol;
-                    const bf16x4 lo = *(const bf16x4*)vr;
-                    const bf16x4 hi = *(const bf16x4*)(vr + 8);
-                    bf16x8 vf;
-                    vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-                    vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-                    o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t w = Pprev[qb][s2][e];
+                    const f32x2 pp = {__uint_as_float(w << 16) * corr, __uint_as_float(w & 0xffff0000u) * corr};
+                    Pprev[qb][s2][e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
                 }
+        }
+    };
+    auto outgrown = [&](const float (&mx)[2]) -> bool {
+        const bool grow = (mx[0] * scale_log2e > m_run[0] + FA_SLACK) || (mx[1] * scale_log2e > m_run[1] + FA_SLACK);
+        return __builtin_amdgcn_ballot_w64(grow) != 0;
+    };
+    auto fenced_barrier = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- prologue: tiles 0 and 1 requested, S of block 0
+    issue_tile(0);
+    if (n_tiles > 1) issue_tile(1);
+    f32x16 Sa[2], Sb[2];
+    float mxa[2], mxb[2];
+    u32x4 Pa[2][2], Pb[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) Pb[qb][s2] = u32x4{0u, 0u, 0u, 0u};
+    __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);        // everything requested so far has landed (whatever order it was issued in)
+    fenced_barrier();
+    first_scores(ring, Sa);
+    mask_block(Sa, 0, mxa);                        // block 0 always meets the diagonal or lies below it: cheap either way
+
+    // ---- tile t2: blocks 2 t2 (kb 0, scores in Sa) and 2 t2 + 1 (kb 1, scores in Sb)
+    for (int t2 = 0; t2 < n_tiles; ++t2) {
+        const unsigned char* cur = ring + (t2 & (FA_SLOTS - 1)) * SLOT;
+        const unsigned char* prev = ring + ((t2 > 0 ? t2 - 1 : 0) & (FA_SLOTS - 1)) * SLOT;
+        const int t_next = min(t2 + 1, n_tiles - 1);
+        const unsigned char* next = ring + (t_next & (FA_SLOTS - 1)) * SLOT;
+        // tile t2+1 (requested one tile ago) has landed; every wave has left tile t2-2, whose slot takes tile t2+2
+        __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);
+        fenced_barrier();
+        if (t2 + 2 < n_tiles) issue_tile(t2 + 2);
+
+        // block 2 t2: the matrix pipe computes S of this tile's second block and O += V P of the previous tile's second
+        // block (t2 = 0: P = 0 against the finite values of tile 0)
+        if (__builtin_expect(outgrown(mxa), 0)) move_reference(mxa, Pb);
+        step(cur, prev, next, std::integral_constant<int, 1>{}, Sa, Sb, Pb, Pa, mxb);
+        if (t2 * FA_BK + 63 > wave_first_pos) mask_block(Sb, t2 * FA_BK + 32, mxb);
+
+        // block 2 t2 + 1: S of the next tile's first block (the last tile recomputes its own; unused) and O += V P of kb 0
+        if (__builtin_expect(outgrown(mxb), 0)) move_reference(mxb, Pa);
+        step(next, cur, next, std::integral_constant<int, 0>{}, Sb, Sa, Pa, Pb, mxa);
+        if (t_next * FA_BK + 31 > wave_first_pos) mask_block(Sa, t_next * FA_BK, mxa);
+    }
+    // O += V P of the last block
+    {
+        const unsigned char* last = ring + ((n_tiles - 1) & (FA_SLOTS - 1)) * SLOT;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                const bf16x8 vf = *(const bf16x8*)(last + v_off[1][s2] + b * 4096);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+                    o[b][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, Pb[qb][s2]), o[b][qb], 0, 0, 0);
             }
     }
 
-    // ---- normalise and store: lane holds query q_local, channels b*32 + 8*(r/4) + 4*half + r%4
-    const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
-    const float inv = 1.0f / l_tot;
-    if (q_local < t.q_rows) {
-        const int64_t orow = t.q_row0 + q_local;
+    // ---- normalise and store: lane holds query qb*32 + lq of its sub-tile, channels b*32 + 8*(r/4) + 4*half + r%4
 #pragma unroll
-        for (int b = 0; b < DB; ++b)
+    for (int qb = 0; qb < 2; ++qb) {
+        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, WAVE);
+        const float inv = 1.0f / l_tot;
+        const int q_local = qs * FA_QW + qb * 32 + lq;
+        if (q_local < t.q_rows) {
+            const int64_t orow = t.q_row0 + q_local;
 #pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                bf16x4 v;
+            for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[b][rg * 4 + e] * inv);
-                const int col = head * HD + b * 32 + rg * 8 + half * 4;            // 4 | 32: never straddles a piece
-                *(bf16x4*)(out + (out_tiled ? tiled_off(orow, col, (int64_t)hq * HD) : orow * hq * HD + col)) = v;
-            }
+                for (int rg = 0; rg < 4; ++rg) {
+                    bf16x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[b][qb][rg * 4 + e] * inv);
+                    const int col = head * HD + b * 32 + rg * 8 + half * 4;        // 4 | 32: never straddles a piece
+                    *(bf16x4*)(out + (out_tiled ? tiled_off(orow, col, (int64_t)hq * HD) : orow * hq * HD + col)) = v;
+                }
+        }
     }
+#endif
+}
+
+template <int HD>
+static void launch_hd(const bf16* qkv, int64_t n_rows, const bf16* vt, int64_t ldv, const AttnTile* tiles, int n_tiles, bf16* out,
+                      int hq, int hkv, float scale_log2e, bool out_tiled, hipStream_t s) {
+    const int hpw = attn_mfma_heads_per_wg(hq, hkv);
+    const unsigned grid = (unsigned)n_tiles * (unsigned)(hq / hpw);
+    if (hpw == 4) attn_mfma_kernel<HD, 4><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
+    else if (hpw == 2) attn_mfma_kernel<HD, 2><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
+    else attn_mfma_kernel<HD, 1><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
 }
 
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
                       void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled) {
     if (n_tiles <= 0) return;
     const float scale_log2e = (1.0f / sqrtf((float)hd)) * 1.4426950408889634f;
-    dim3 grid((unsigned)n_tiles, (unsigned)hq);
-    if (hd == 128)
-        attn_mfma_kernel<128><<<grid, FA_THREADS, 0, s>>>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, (bf16*)out, hq,
-                                                          hkv, scale_log2e, out_tiled);
-    else
-        attn_mfma_kernel<64><<<grid, FA_THREADS, 0, s>>>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, (bf16*)out, hq,
-                                                         hkv, scale_log2e, out_tiled);
+    if (hd == 128) launch_hd<128>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, n_tiles, (bf16*)out, hq, hkv, scale_log2e, out_tiled, s);
+    else launch_hd<64>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, n_tiles, (bf16*)out, hq, hkv, scale_log2e, out_tiled, s);
 }
 
 }  // namespace vl
