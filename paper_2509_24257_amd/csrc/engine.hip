@@ -47,6 +47,9 @@ bool check_cfg(const vl_model_cfg* c, std::string& why) {
     if (c->dtype == VL_BF16) {
         if (c->d_model % 64 || qd % 64 || c->d_ffn % 64) { why = "bf16 models need d_model, n_q_heads*head_dim, d_ffn multiples of 64"; return false; }
         if (c->head_dim != 128 && c->head_dim != 64) { why = "bf16 models need head_dim 64 or 128"; return false; }
+        if (!attn_mfma_fits(c->n_q_heads, c->n_kv_heads, c->head_dim, c->max_seq_len)) {
+            why = "max_seq_len too large: the q/k/v rows of one sequence must span less than 4 GB"; return false;
+        }
     } else {
         if (c->d_model % 8 || c->d_ffn % 16 || c->head_dim % 4 || c->head_dim > 256) {
             why = "f32 models need d_model % 8 == 0, d_ffn % 16 == 0, head_dim % 4 == 0, head_dim <= 256"; return false;

@@ -87,6 +87,8 @@ struct AttnTile { int32_t q_row0, q_rows, kv_row0, kv_len, vt_col0, pos0; };  //
 //   visible to the tile, vt_col0 column of the sequence's first token in vt (a multiple of 8)
 // Queries per tile for this head geometry: 64, 128 or 256 (a workgroup serves 4, 2 or 1 query heads of one KV head).
 int attn_mfma_q_span(int hq, int hkv);
+// The kernel addresses a sequence's keys with 32-bit byte offsets: the longest sequence it can take.
+bool attn_mfma_fits(int hq, int hkv, int hd, int64_t max_seq_len);
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
                       void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled = false);
 

@@ -100,30 +100,31 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     const int n_tiles = (t.kv_len + FA_BK - 1) / FA_BK;
     const bf16* kseq = qkv + (int64_t)t.kv_row0 * pitch + (int64_t)hq * HD + (int64_t)g * HD;
     const bf16* vseq = vt + (int64_t)g * HD * ldv + t.vt_col0;
-    const int k_last = (int)(n_rows - 1 - t.kv_row0);                 // rows past the buffer re-read its last row (masked)
-    const uint32_t k_bytes = (uint32_t)min((int64_t)(k_last + 1) * pitch * 2 - (int64_t)(hq + g) * HD * 2, (int64_t)0xFFFFFFFFll);
-    const uint32_t v_bytes = (uint32_t)(((int64_t)HD * ldv - t.vt_col0) * 2);
-    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kseq, 0, k_bytes, 0x00020000);
-    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vseq, 0, v_bytes, 0x00020000);
+    // bytes from those two addresses to the end of their buffers (saturated; a sequence spans less than 4 GB, which
+    // the launcher checks): a descriptor that starts at a tile and ends with the buffer makes rows past the end read
+    // as zeros (they are masked anyway) instead of needing a clamp per lane
+    const uint32_t k_total = (uint32_t)min(((int64_t)(n_rows - t.kv_row0) * pitch - (int64_t)(hq + g) * HD) * 2, (int64_t)0xFFFFFFFFll);
+    const uint32_t v_total = (uint32_t)min(((int64_t)HD * ldv - t.vt_col0) * 2, (int64_t)0xFFFFFFFFll);
+    const uint32_t row_bytes = (uint32_t)pitch * 2;
     const int k_row = wave * K_RPI + lane / KCPR;                     // + 4 * K_RPI * i
     const int k_swz = KCPR == 16 ? (k_row & 15) : ((k_row >> 1) & 7);
-    const uint32_t k_col = ((lane % KCPR) ^ k_swz) * 16;              // bytes
-    const uint32_t row_bytes = (uint32_t)pitch * 2;
     const int v_row = wave * 8 + (lane >> 3);                         // + 32 * i
-    uint32_t v_lane[NI_V];
+    uint32_t k_lane[NI_K], v_lane[NI_V];                              // byte offsets from the tile's first key, per lane
+#pragma unroll
+    for (int i = 0; i < NI_K; ++i) k_lane[i] = (uint32_t)(k_row + 4 * K_RPI * i) * row_bytes + ((lane % KCPR) ^ k_swz) * 16;
 #pragma unroll
     for (int i = 0; i < NI_V; ++i) v_lane[i] = (uint32_t)(v_row + 32 * i) * (uint32_t)ldv * 2 + ((lane & 7) ^ ((v_row >> 1) & 7)) * 16;
-    auto issue_tile = [&](int tile) {
+    auto issue_tile = [&](int tile) {                                 // everything but the lane offsets is scalar
         unsigned char* slot = ring + (tile & (FA_SLOTS - 1)) * SLOT + wave * 1024;
-        const int key0 = tile * FA_BK;
+        const uint32_t k_skip = (uint32_t)tile * FA_BK * row_bytes, v_skip = (uint32_t)tile * FA_BK * 2;
+        const uint32_t k_left = k_total > k_skip ? k_total - k_skip : 0u, v_left = v_total > v_skip ? v_total - v_skip : 0u;
+        const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)kseq + k_skip), 0, k_left, 0x00020000);
+        const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)vseq + v_skip), 0, v_left, 0x00020000);
 #pragma unroll
-        for (int i = 0; i < NI_K; ++i) {
-            const uint32_t row = (uint32_t)min(key0 + k_row + 4 * K_RPI * i, k_last);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, FA_LDS(slot + i * 4096), 16, row * row_bytes + k_col, 0, 0, 0);
-        }
+        for (int i = 0; i < NI_K; ++i) __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, FA_LDS(slot + i * 4096), 16, k_lane[i], 0, 0, 0);
 #pragma unroll
         for (int i = 0; i < NI_V; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, FA_LDS(slot + K_BYTES + i * 4096), 16, v_lane[i] + (uint32_t)key0 * 2, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, FA_LDS(slot + K_BYTES + i * 4096), 16, v_lane[i], 0, 0, 0);
     };
 
     // ---- fragment read offsets inside a slot
@@ -156,16 +157,14 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     //   fragment i (K fragments first, then V^T fragments) feeds slots 2 i and 2 i + 1 and is read FA_AHEAD fragments
     //   early into a ring of eight registers quads; the last reads of a step are the first K fragments of the NEXT
     //   step (block 1 - KB of the tile in `nkslot`), so no step starts by waiting for LDS
-    //   vector work: slot e turns score(s) e of S_cur into probabilities; every second score closes a pair (row sum,
-    //   rounding to bf16).  The lane maxima of S_next are taken in the last slots, at least four matrix instructions
-    //   after the last one that wrote S_next.
+    //   vector work: slot e turns score(s) e of S_cur into probabilities; every second score closes a pair (rounding
+    //   to bf16, row sum of the rounded values)
     constexpr int NS = 2 * KSTEPS, NSLOT = NS + 4 * DB, NFRAG = NSLOT / 2;
     constexpr int FA_AHEAD = HD == 128 ? 5 : 4;      // <= KSTEPS: the early reads for the next step are all K fragments
     constexpr int EPS = 32 / NSLOT;                // scores per slot (1 or 2)
-    constexpr int MAX0 = HD == 128 ? NSLOT - 8 : NSLOT - 4, MAX_PER = 16 / (NSLOT - MAX0);
     bf16x8 fr[8];
     auto step = [&](const unsigned char* kslot, const unsigned char* vslot, const unsigned char* nkslot, auto kb_c,
-                    const f32x16 (&Sc)[2], f32x16 (&Sn)[2], const u32x4 (&Pp)[2][2], u32x4 (&Pc)[2][2], float (&mx)[2]) {
+                    const f32x16 (&Sc)[2], f32x16 (&Sn)[2], const u32x4 (&Pp)[2][2], u32x4 (&Pc)[2][2]) {
         constexpr int KB = decltype(kb_c)::value;
         auto read_frag = [&](int i) {
             if (i < KSTEPS) fr[i & 7] = *(const bf16x8*)(kslot + KB * 32 * KROW + k_off[i]);
@@ -173,14 +172,14 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
             else fr[i & 7] = *(const bf16x8*)(nkslot + (1 - KB) * 32 * KROW + k_off[i - NFRAG]);
         };
         float pe[4] = {0.f, 0.f, 0.f, 0.f};
-        float mrun[2] = {-INFINITY, -INFINITY};
-        // closes pair u of S_cur: rounds its two probabilities to bf16 and adds them (as rounded) to the row sum
+        // closes pair u of S_cur: adds its two probabilities to the row sum and rounds them to bf16.  (Plain adds: the
+        // packed dot-product instructions share the matrix pipe and would not run beside the MFMAs.)
         auto close_pair = [&](int u) {
             const int eq = u >> 3, r0 = 2 * (u & 7);
             const f32x2 pp = {pe[(2 * u) & 3], pe[(2 * u + 1) & 3]};
-            const bf16x2 w = __builtin_convertvector(pp, bf16x2);
-            l_run[eq] = __builtin_amdgcn_fdot2_f32_bf16(w, __builtin_bit_cast(bf16x2, 0x3F803F80u), l_run[eq], false);
-            uint32_t wi = __builtin_bit_cast(uint32_t, w);
+            l_run[eq] += pp[0];
+            l_run[eq] += pp[1];
+            uint32_t wi = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
             asm volatile("" : "+v"(l_run[eq]), "+v"(wi));             // pinned to this slot: nothing may sink below
             Pc[eq][r0 >> 3][(r0 & 7) >> 1] = wi;
         };
@@ -205,86 +204,40 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
                 pe[e & 3] = __builtin_amdgcn_exp2f(__builtin_fmaf(Sc[eq][r], scale_log2e, -m_run[eq]));
                 asm volatile("" : "+v"(pe[e & 3]));
             }
-            if (slot >= MAX0) {
-#pragma unroll
-                for (int k = 0; k < MAX_PER; ++k) {
-                    const int op = (slot - MAX0) * MAX_PER + k, mq = op & 1, n = op >> 1;   // eight steps per query block
-                    if (n == 0) asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(mrun[mq]) : "v"(Sn[mq][0]), "v"(Sn[mq][1]), "v"(Sn[mq][2]));
-                    else if (n < 7) asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(mrun[mq]) : "v"(Sn[mq][2 * n + 1]), "v"(Sn[mq][2 * n + 2]));
-                    else asm volatile("v_max_f32 %0, %0, %1" : "+v"(mrun[mq]) : "v"(Sn[mq][15]));
-                }
-            }
             __builtin_amdgcn_sched_barrier(0);
         }
         close_pair(15);
-        mx[0] = mrun[0];
-        mx[1] = mrun[1];
     };
-    // S^T of the first block (nothing to overlap with yet)
-    auto first_scores = [&](const unsigned char* slot, f32x16 (&S)[2]) {
+    // S^T of one block outside the pipeline (the first block; the rare second pass over the scores)
+    auto block_scores = [&](const unsigned char* slot, int kb, f32x16 (&S)[2]) {
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
-            const bf16x8 kf = *(const bf16x8*)(slot + k_off[s]);
+            const bf16x8 kf = *(const bf16x8*)(slot + kb * 32 * KROW + k_off[s]);
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
                 if (s == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(S[qb]) : "v"(kf), "a"(qf[qb][s]));
                 else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(S[qb]) : "v"(kf), "a"(qf[qb][s]));
             }
         }
-        // the first fragments of the first pipeline step (second block of the same tile)
-#pragma unroll
-        for (int i = 0; i < FA_AHEAD; ++i) fr[i] = *(const bf16x8*)(slot + 32 * KROW + k_off[i]);
         // the results of these hand-issued instructions are not tracked by the compiler: let the last one drain
         asm volatile("s_nop 15\n\ts_nop 7" : "+v"(S[0]), "+v"(S[1]));
     };
-    // causal mask of a block that reaches past the wave's first query, and the lane maxima again
-    auto mask_block = [&](f32x16 (&S)[2], int key0, float (&mx)[2]) {
+    // causal mask of a block that reaches past the wave's first query
+    auto mask_block = [&](f32x16 (&S)[2], int key0) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const int d = q_pos[qb] - key0 - 8 * half;                // key of register r = key0 + 8*half + 16*(r/8) + r%8
-            float m = -INFINITY;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 16; ++r)
                 if (16 * (r >> 3) + (r & 7) > d) S[qb][r] = -INFINITY;
-                m = fmaxf(m, S[qb][r]);
-            }
-            mx[qb] = m;
         }
     };
-    // rare path: some query's block maximum has outgrown its reference.  The new reference is the joint maximum of
-    // both lane halves; O, l and the probabilities that have not been multiplied into O yet move with it.
-    auto move_reference = [&](const float (&mx)[2], u32x4 (&Pprev)[2][2]) {
+    // this lane's maxima of a block's raw scores, folded into mx
+    auto block_max = [&](const f32x16 (&S)[2], float (&mx)[2]) {
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float m_blk = fmaxf(mx[qb], __shfl_xor(mx[qb], 32, WAVE)) * scale_log2e;
-            const float m_new = fmaxf(m_run[qb], m_blk);              // finite: the first block holds key 0
-            const float corr = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-            m_run[qb] = m_new;
-            l_run[qb] *= corr;
-            // O lives in accumulation registers, which only these three instructions can touch; written out so that
-            // the copies stay on this path instead of being hoisted into the loop
+        for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float x = o[b][qb][r], tmp;
-                    asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 %0, %1"
-                                 : "+a"(x), "=&v"(tmp) : "v"(corr));
-                    o[b][qb][r] = x;
-                }
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t w = Pprev[qb][s2][e];
-                    const f32x2 pp = {__uint_as_float(w << 16) * corr, __uint_as_float(w & 0xffff0000u) * corr};
-                    Pprev[qb][s2][e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-                }
-        }
-    };
-    auto outgrown = [&](const float (&mx)[2]) -> bool {
-        const bool grow = (mx[0] * scale_log2e > m_run[0] + FA_SLACK) || (mx[1] * scale_log2e > m_run[1] + FA_SLACK);
-        return __builtin_amdgcn_ballot_w64(grow) != 0;
+            for (int r = 0; r < 16; ++r) mx[qb] = fmaxf(mx[qb], S[qb][r]);
     };
     auto fenced_barrier = [&]() {
         __builtin_amdgcn_sched_barrier(0);
@@ -292,75 +245,159 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- prologue: tiles 0 and 1 requested, S of block 0
-    issue_tile(0);
-    if (n_tiles > 1) issue_tile(1);
-    f32x16 Sa[2], Sb[2];
-    float mxa[2], mxb[2];
-    u32x4 Pa[2][2], Pb[2][2];
+    // The exponent reference of a query is fixed before the key loop: the maximum of its first 32 scores.  Later
+    // scores may exceed it; the probabilities then exceed 1, which is harmless until they overflow.  Each step only
+    // notes whether a lane's block of 16 probabilities summed to more than 16 * 2^FA_SLACK (or to something that is not
+    // a number).  If any wave of the workgroup noted that, the workgroup runs again with the exact row maxima as
+    // references, found by one extra pass over the scores; then no probability exceeds 1.
+    __shared__ int vote;
+    if (tid == 0) vote = 0;
+    bool noted = false;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        float mx[2] = {-INFINITY, -INFINITY};
+        f32x16 Sa[2], Sb[2];
+        if (attempt == 1) {
+            // second pass: exact row maxima over all keys
+            for (int t2 = 0; t2 < n_tiles; ++t2) {
+                const unsigned char* cur = ring + (t2 & (FA_SLOTS - 1)) * SLOT;
+                issue_tile(t2);
+                __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);
+                fenced_barrier();
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) Pb[qb][s2] = u32x4{0u, 0u, 0u, 0u};
-    __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);        // everything requested so far has landed (whatever order it was issued in)
-    fenced_barrier();
-    first_scores(ring, Sa);
-    mask_block(Sa, 0, mxa);                        // block 0 always meets the diagonal or lies below it: cheap either way
-
-    // ---- tile t2: blocks 2 t2 (kb 0, scores in Sa) and 2 t2 + 1 (kb 1, scores in Sb)
-    for (int t2 = 0; t2 < n_tiles; ++t2) {
-        const unsigned char* cur = ring + (t2 & (FA_SLOTS - 1)) * SLOT;
-        const unsigned char* prev = ring + ((t2 > 0 ? t2 - 1 : 0) & (FA_SLOTS - 1)) * SLOT;
-        const int t_next = min(t2 + 1, n_tiles - 1);
-        const unsigned char* next = ring + (t_next & (FA_SLOTS - 1)) * SLOT;
-        // tile t2+1 (requested one tile ago) has landed; every wave has left tile t2-2, whose slot takes tile t2+2
-        __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);
-        fenced_barrier();
-        if (t2 + 2 < n_tiles) issue_tile(t2 + 2);
-
-        // block 2 t2: the matrix pipe computes S of this tile's second block and O += V P of the previous tile's second
-        // block (t2 = 0: P = 0 against the finite values of tile 0)
-        if (__builtin_expect(outgrown(mxa), 0)) move_reference(mxa, Pb);
-        step(cur, prev, next, std::integral_constant<int, 1>{}, Sa, Sb, Pb, Pa, mxb);
-        if (t2 * FA_BK + 63 > wave_first_pos) mask_block(Sb, t2 * FA_BK + 32, mxb);
-
-        // block 2 t2 + 1: S of the next tile's first block (the last tile recomputes its own; unused) and O += V P of kb 0
-        if (__builtin_expect(outgrown(mxb), 0)) move_reference(mxb, Pa);
-        step(next, cur, next, std::integral_constant<int, 0>{}, Sb, Sa, Pa, Pb, mxa);
-        if (t_next * FA_BK + 31 > wave_first_pos) mask_block(Sa, t_next * FA_BK, mxa);
-    }
-    // O += V P of the last block
-    {
-        const unsigned char* last = ring + ((n_tiles - 1) & (FA_SLOTS - 1)) * SLOT;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int b = 0; b < DB; ++b) {
-                const bf16x8 vf = *(const bf16x8*)(last + v_off[1][s2] + b * 4096);
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
-                    o[b][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, Pb[qb][s2]), o[b][qb], 0, 0, 0);
+                for (int kb = 0; kb < 2; ++kb) {
+                    block_scores(cur, kb, Sa);
+                    if (t2 * FA_BK + 32 * kb + 31 > wave_first_pos) mask_block(Sa, t2 * FA_BK + 32 * kb);
+                    block_max(Sa, mx);
+                }
             }
+            fenced_barrier();                      // every wave is done with the ring before it is refilled
+        }
+
+        // ---- tiles 0 and 1 requested, S of block 0
+        issue_tile(0);
+        if (n_tiles > 1) issue_tile(1);
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[b][qb][r] = 0.f;
+        u32x4 Pa[2][2], Pb[2][2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) Pb[qb][s2] = u32x4{0u, 0u, 0u, 0u};
+        __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);    // everything requested so far has landed (whatever order it was issued in)
+        fenced_barrier();
+        block_scores(ring, 0, Sa);
+        mask_block(Sa, 0);                         // block 0 always meets the diagonal or lies below it: cheap either way
+        if (attempt == 0) block_max(Sa, mx);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {           // key 0 is visible to every query: the maxima are finite
+            m_run[qb] = fmaxf(mx[qb], __shfl_xor(mx[qb], 32, WAVE)) * scale_log2e;
+            l_run[qb] = 0.f;
+        }
+        // the first fragments of the first pipeline step (second block of tile 0)
+        // (issued in this order and as the last LDS reads before the loop, exactly as every step leaves them)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < FA_AHEAD; ++i) {
+            fr[i] = *(const bf16x8*)(ring + 32 * KROW + k_off[i]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // ---- tile t2: blocks 2 t2 (kb 0, scores in Sa) and 2 t2 + 1 (kb 1, scores in Sb)
+        constexpr float bound = 16.0f * (float)(1 << (int)FA_SLACK);
+        for (int t2 = 0; t2 < n_tiles; ++t2) {
+            const unsigned char* cur = ring + (t2 & (FA_SLOTS - 1)) * SLOT;
+            const unsigned char* prev = ring + ((t2 > 0 ? t2 - 1 : 0) & (FA_SLOTS - 1)) * SLOT;
+            const int t_next = min(t2 + 1, n_tiles - 1);
+            const unsigned char* next = ring + (t_next & (FA_SLOTS - 1)) * SLOT;
+            // tile t2+1 (requested one tile ago) has landed; every wave has left tile t2-2, whose slot takes tile t2+2
+            __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);
+            fenced_barrier();
+            if (t2 + 2 < n_tiles) issue_tile(t2 + 2);
+
+            // block 2 t2: the matrix pipe computes S of this tile's second block and O += V P of the previous tile's
+            // second block (t2 = 0: P = 0 against the finite values of tile 0)
+            const float la0 = l_run[0], la1 = l_run[1];
+            step(cur, prev, next, std::integral_constant<int, 1>{}, Sa, Sb, Pb, Pa);
+            noted |= !(l_run[0] - la0 <= bound) | !(l_run[1] - la1 <= bound);       // (also true for a sum that is no number)
+            if (t2 * FA_BK + 63 > wave_first_pos) mask_block(Sb, t2 * FA_BK + 32);
+
+            // block 2 t2 + 1: S of the next tile's first block (the last tile recomputes its own; unused) and O += V P of kb 0
+            const float lb0 = l_run[0], lb1 = l_run[1];
+            step(next, cur, next, std::integral_constant<int, 0>{}, Sb, Sa, Pa, Pb);
+            noted |= !(l_run[0] - lb0 <= bound) | !(l_run[1] - lb1 <= bound);
+            if (t_next * FA_BK + 31 > wave_first_pos) mask_block(Sa, t_next * FA_BK);
+        }
+        // O += V P of the last block
+        {
+            const unsigned char* last = ring + ((n_tiles - 1) & (FA_SLOTS - 1)) * SLOT;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int b = 0; b < DB; ++b) {
+                    const bf16x8 vf = *(const bf16x8*)(last + v_off[1][s2] + b * 4096);
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb)
+                        o[b][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, Pb[qb][s2]), o[b][qb], 0, 0, 0);
+                }
+        }
+        if (attempt == 1) break;
+        // has any wave of the workgroup noted an outgrown reference?  (uniform for the workgroup: all waves repeat together)
+        if (__builtin_amdgcn_ballot_w64(noted) != 0 && lane == 0) vote = 1;
+        fenced_barrier();                          // also: every wave is past its last fragment read
+        if (__builtin_amdgcn_readfirstlane(*(volatile int*)&vote) == 0) break;
     }
 
-    // ---- normalise and store: lane holds query qb*32 + lq of its sub-tile, channels b*32 + 8*(r/4) + 4*half + r%4
+    // ---- normalise, transpose through LDS (the ring is free once every wave is past its last fragment read) and store
+    // whole 16-byte pieces: lane holds query qb*32 + lq of its sub-tile, channels b*32 + 8*(r/4) + 4*half + r%4
+    constexpr int OP = HD * 2 + 8;                 // row pitch of the staging rows: 8-byte writes of 32 lanes hit 64 banks
+    fenced_barrier();
+    unsigned char* stage = ring + wave * (FA_QW * OP);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, WAVE);
-        const float inv = 1.0f / l_tot;
-        const int q_local = qs * FA_QW + qb * 32 + lq;
-        if (q_local < t.q_rows) {
-            const int64_t orow = t.q_row0 + q_local;
+        const float inv = 1.0f / (l_run[qb] + __shfl_xor(l_run[qb], 32, WAVE));
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+        for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int rg = 0; rg < 4; ++rg) {
-                    bf16x4 v;
+            for (int rg = 0; rg < 4; ++rg) {
+                bf16x4 v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[b][qb][rg * 4 + e] * inv);
-                    const int col = head * HD + b * 32 + rg * 8 + half * 4;        // 4 | 32: never straddles a piece
-                    *(bf16x4*)(out + (out_tiled ? tiled_off(orow, col, (int64_t)hq * HD) : orow * hq * HD + col)) = v;
+                for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[b][qb][rg * 4 + e] * inv);
+                *(bf16x4*)(stage + (qb * 32 + lq) * OP + (b * 32 + rg * 8 + half * 4) * 2) = v;
+            }
+    }
+    // (a wave reads back only what it wrote itself: no barrier)
+    const int q_valid = t.q_rows - qs * FA_QW;     // rows of this wave's sub-tile that exist
+    const int64_t orow0 = t.q_row0 + qs * FA_QW;
+    if (out_tiled) {
+        // tiled image: for one k-tile of 32 channels, consecutive rows are 64 bytes apart -> 16 rows = 1 KB per instruction
+#pragma unroll
+        for (int kt = 0; kt < HD / 32; ++kt)
+#pragma unroll
+            for (int i = 0; i < FA_QW / 16; ++i) {
+                const int q = 16 * i + (lane >> 2), c = kt * 32 + (lane & 3) * 8;
+                const bf16x4 lo = *(const bf16x4*)(stage + q * OP + c * 2), hi = *(const bf16x4*)(stage + q * OP + c * 2 + 8);
+                if (q < q_valid) {
+                    bf16* dst = out + tiled_off(orow0 + q, head * HD + c, (int64_t)hq * HD);
+                    *(bf16x4*)dst = lo;
+                    *(bf16x4*)(dst + 4) = hi;
                 }
+            }
+    } else {
+        // row-major: a row of this head is HD * 2 contiguous bytes
+        constexpr int LPR = HD / 8;                // lanes per row
+#pragma unroll
+        for (int i = 0; i < FA_QW / (64 / LPR); ++i) {
+            const int q = (64 / LPR) * i + lane / LPR, c = (lane % LPR) * 8;
+            const bf16x4 lo = *(const bf16x4*)(stage + q * OP + c * 2), hi = *(const bf16x4*)(stage + q * OP + c * 2 + 8);
+            if (q < q_valid) {
+                bf16* dst = out + (orow0 + q) * hq * HD + head * HD + c;
+                *(bf16x4*)dst = lo;
+                *(bf16x4*)(dst + 4) = hi;
+            }
         }
     }
 #endif
@@ -374,6 +411,10 @@ static void launch_hd(const bf16* qkv, int64_t n_rows, const bf16* vt, int64_t l
     if (hpw == 4) attn_mfma_kernel<HD, 4><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
     else if (hpw == 2) attn_mfma_kernel<HD, 2><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
     else attn_mfma_kernel<HD, 1><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
+}
+
+bool attn_mfma_fits(int hq, int hkv, int hd, int64_t max_seq_len) {
+    return max_seq_len * (int64_t)(hq + 2 * hkv) * hd * 2 < (int64_t)0xFFFFFFFFll;
 }
 
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,

@@ -225,11 +225,17 @@ def test_gemm_bf16_matches_float64_product(ctx_small_bf16, M, N, K, out_dtype):
 
 
 # ------------------------------------------------------------------ matrix-core causal GQA attention
-def _attention_case(ctx, m, lengths, seed):
+def _attention_case(ctx, m, lengths, seed, late_key_gain=1.0):
     hq, hkv, hd = m.n_q_heads, m.n_kv_heads, m.head_dim
     n = sum(lengths)
     rng = np.random.default_rng(seed)
     qkv = (rng.standard_normal((n, (hq + 2 * hkv) * hd)) * 1.5).astype(np.float32)
+    if late_key_gain != 1.0:
+        # keys from position 40 on are much larger than the first ones: scores far above those of the first key block
+        lo = 0
+        for t in lengths:
+            qkv[lo + 40:lo + t, hq * hd:(hq + hkv) * hd] *= late_key_gain
+            lo += t
     bits = synth.f32_to_bf16_bits(qkv)
     vals = O.upcast(bits)
     d_qkv = H.to_dev(bits)
@@ -265,6 +271,15 @@ def test_attention_hd128_gqa4_matches_oracle(ctx_hd128, lengths):
     ctx, m = ctx_hd128
     say(f"attention hd128 lengths={lengths}")
     assert _attention_case(ctx, m, lengths, 2) < 3e-2
+
+
+@pytest.mark.parametrize("gain", [6.0, 40.0])
+def test_attention_scores_far_above_the_first_block(ctx_hd128, ctx_small_bf16, gain):
+    """The kernel fixes a query's exponent reference on its first 32 keys and repeats a workgroup with exact row maxima
+    when later scores outgrow it (gain 6: by dozens of binary orders; gain 40: beyond the range of float32 exponentials)."""
+    for (ctx, m), lengths in ((ctx_hd128, [300, 129, 64]), (ctx_small_bf16, [520, 70])):
+        say(f"attention with late keys x{gain}, head_dim {m.head_dim}, lengths={lengths}")
+        assert _attention_case(ctx, m, lengths, 5, late_key_gain=gain) < 3e-2
 
 
 # ------------------------------------------------------------------ attention of the token-by-token path
