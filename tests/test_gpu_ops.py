@@ -273,6 +273,21 @@ def test_attention_hd128_gqa4_matches_oracle(ctx_hd128, lengths):
     assert _attention_case(ctx, m, lengths, 2) < 3e-2
 
 
+@pytest.mark.parametrize("hq,hkv,hd", [(4, 2, 128), (8, 1, 128), (6, 2, 64), (16, 2, 64), (2, 2, 128)])
+def test_attention_head_groupings_match_oracle(hq, hkv, hd):
+    """A workgroup of the prefill attention kernel serves 4, 2 or 1 query heads of one KV head (group sizes that are
+    multiples of 4, even, odd), with query tiles of 64, 128 or 256 rows; every such mapping against the oracle, on
+    lengths that leave ragged last tiles."""
+    say(f"attention hq={hq} hkv={hkv} hd={hd}")
+    m = synth.small_model("bf16", n_layers=1, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, d_model=256)
+    lengths = [300, 64, 1, 257, 129]
+    ctx = P.Context(H.c_cfg(m, sum(lengths), len(lengths), max(lengths)), 0, 0)        # op calls need no weights
+    try:
+        assert _attention_case(ctx, m, lengths, hq * 100 + hkv * 10 + hd) < 3e-2
+    finally:
+        ctx.close()
+
+
 @pytest.mark.parametrize("gain", [6.0, 40.0])
 def test_attention_scores_far_above_the_first_block(ctx_hd128, ctx_small_bf16, gain):
     """The kernel fixes a query's exponent reference on its first 32 keys and repeats a workgroup with exact row maxima
