@@ -114,17 +114,34 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     for (int i = 0; i < NI_K; ++i) k_lane[i] = (uint32_t)(k_row + 4 * K_RPI * i) * row_bytes + ((lane % KCPR) ^ k_swz) * 16;
 #pragma unroll
     for (int i = 0; i < NI_V; ++i) v_lane[i] = (uint32_t)(v_row + 32 * i) * (uint32_t)ldv * 2 + ((lane & 7) ^ ((v_row >> 1) & 7)) * 16;
-    auto issue_tile = [&](int tile) {                                 // everything but the lane offsets is scalar
-        unsigned char* slot = ring + (tile & (FA_SLOTS - 1)) * SLOT + wave * 1024;
+    // One tile = NI_K + NI_V load instructions per wave (buffer loads that write LDS directly: 64 lanes x 16 bytes land at
+    // M0 + 16 * lane).  They are written out by hand: the compiler would order every later LDS read behind a full wait
+    // for a load of this kind that it knows of, which defeats spreading the loads over the slots of a step (issued back
+    // to back they hold the wave for some 400 cycles per tile).  Completion is awaited explicitly: s_waitcnt vmcnt(0)
+    // before the barrier that publishes a tile.  The descriptors are scalar; a tile that does not exist gets empty
+    // ones, so its loads touch no memory (they fill a free slot with zeros) and the code needs no branch.
+    constexpr int NPIECE = NI_K + NI_V;
+    auto tile_descriptors = [&](int tile, u32x4& k_rsrc, u32x4& v_rsrc) {
         const uint32_t k_skip = (uint32_t)tile * FA_BK * row_bytes, v_skip = (uint32_t)tile * FA_BK * 2;
-        const uint32_t k_left = k_total > k_skip ? k_total - k_skip : 0u, v_left = v_total > v_skip ? v_total - v_skip : 0u;
-        const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)kseq + k_skip), 0, k_left, 0x00020000);
-        const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)vseq + v_skip), 0, v_left, 0x00020000);
+        const bool there = tile < n_tiles;
+        const uint32_t k_left = (there && k_total > k_skip) ? k_total - k_skip : 0u, v_left = (there && v_total > v_skip) ? v_total - v_skip : 0u;
+        const uint64_t ka = (uint64_t)kseq + k_skip, va = (uint64_t)vseq + v_skip;
+        // raw buffer descriptor: base, stride 0, bytes, data format
+        auto uni = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_readfirstlane(x); };
+        k_rsrc = u32x4{uni((uint32_t)ka), uni((uint32_t)(ka >> 32) & 0xffffu), uni(k_left), 0x00020000u};
+        v_rsrc = u32x4{uni((uint32_t)va), uni((uint32_t)(va >> 32) & 0xffffu), uni(v_left), 0x00020000u};
+    };
+    const uint32_t ring_lds = (uint32_t)(uintptr_t)FA_LDS(ring) + wave * 1024;
+    auto issue_piece = [&](int tile, int piece, const u32x4& k_rsrc, const u32x4& v_rsrc) {
+        const uint32_t dst = ring_lds + (tile & (FA_SLOTS - 1)) * SLOT + (piece < NI_K ? piece * 4096 : K_BYTES + (piece - NI_K) * 4096);
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+                     :: "v"(piece < NI_K ? k_lane[piece] : v_lane[piece - NI_K]), "s"(piece < NI_K ? k_rsrc : v_rsrc), "s"(dst));
+    };
+    auto issue_tile = [&](int tile) {
+        u32x4 k_rsrc, v_rsrc;
+        tile_descriptors(tile, k_rsrc, v_rsrc);
 #pragma unroll
-        for (int i = 0; i < NI_K; ++i) __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, FA_LDS(slot + i * 4096), 16, k_lane[i], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < NI_V; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, FA_LDS(slot + K_BYTES + i * 4096), 16, v_lane[i], 0, 0, 0);
+        for (int i = 0; i < NPIECE; ++i) issue_piece(tile, i, k_rsrc, v_rsrc);
     };
 
     // ---- fragment read offsets inside a slot
@@ -157,6 +174,8 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     //   fragment i (K fragments first, then V^T fragments) feeds slots 2 i and 2 i + 1 and is read FA_AHEAD fragments
     //   early into a ring of eight registers quads; the last reads of a step are the first K fragments of the NEXT
     //   step (block 1 - KB of the tile in `nkslot`), so no step starts by waiting for LDS
+    //   every_slot(slot): the caller's share of other work (the first step of a tile spreads the loads of the tile after
+    //   next over its slots)
     //   vector work: slot e turns score(s) e of S_cur into probabilities; every second score closes a pair (rounding
     //   to bf16, row sum of the rounded values)
     constexpr int NS = 2 * KSTEPS, NSLOT = NS + 4 * DB, NFRAG = NSLOT / 2;
@@ -164,7 +183,7 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     constexpr int EPS = 32 / NSLOT;                // scores per slot (1 or 2)
     bf16x8 fr[8];
     auto step = [&](const unsigned char* kslot, const unsigned char* vslot, const unsigned char* nkslot, auto kb_c,
-                    const f32x16 (&Sc)[2], f32x16 (&Sn)[2], const u32x4 (&Pp)[2][2], u32x4 (&Pc)[2][2]) {
+                    const f32x16 (&Sc)[2], f32x16 (&Sn)[2], const u32x4 (&Pp)[2][2], u32x4 (&Pc)[2][2], auto&& every_slot) {
         constexpr int KB = decltype(kb_c)::value;
         auto read_frag = [&](int i) {
             if (i < KSTEPS) fr[i & 7] = *(const bf16x8*)(kslot + KB * 32 * KROW + k_off[i]);
@@ -187,6 +206,7 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
         for (int slot = 0; slot < NSLOT; ++slot) {
             const int i = slot >> 1, qb = slot & 1;
             if (qb == 0) read_frag(i + FA_AHEAD);
+            every_slot(slot);
             // ---- matrix pipe
             if (slot < NS) {
                 if (i == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(Sn[qb]) : "v"(fr[i & 7]), "a"(qf[qb][i]));
@@ -316,18 +336,22 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
             // tile t2+1 (requested one tile ago) has landed; every wave has left tile t2-2, whose slot takes tile t2+2
             __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);
             fenced_barrier();
-            if (t2 + 2 < n_tiles) issue_tile(t2 + 2);
+            u32x4 k_rsrc, v_rsrc;
+            tile_descriptors(t2 + 2, k_rsrc, v_rsrc);
 
             // block 2 t2: the matrix pipe computes S of this tile's second block and O += V P of the previous tile's
             // second block (t2 = 0: P = 0 against the finite values of tile 0)
             const float la0 = l_run[0], la1 = l_run[1];
-            step(cur, prev, next, std::integral_constant<int, 1>{}, Sa, Sb, Pb, Pa);
+            constexpr int every = NSLOT / NPIECE;   // one load instruction every `every` slots
+            step(cur, prev, next, std::integral_constant<int, 1>{}, Sa, Sb, Pb, Pa, [&](int slot) {
+                if (slot % every == every / 2) issue_piece(t2 + 2, slot / every, k_rsrc, v_rsrc);
+            });
             noted |= !(l_run[0] - la0 <= bound) | !(l_run[1] - la1 <= bound);       // (also true for a sum that is no number)
             if (t2 * FA_BK + 63 > wave_first_pos) mask_block(Sb, t2 * FA_BK + 32);
 
             // block 2 t2 + 1: S of the next tile's first block (the last tile recomputes its own; unused) and O += V P of kb 0
             const float lb0 = l_run[0], lb1 = l_run[1];
-            step(next, cur, next, std::integral_constant<int, 0>{}, Sb, Sa, Pa, Pb);
+            step(next, cur, next, std::integral_constant<int, 0>{}, Sb, Sa, Pa, Pb, [](int) {});
             noted |= !(l_run[0] - lb0 <= bound) | !(l_run[1] - lb1 <= bound);
             if (t_next * FA_BK + 31 > wave_first_pos) mask_block(Sa, t_next * FA_BK);
         }
@@ -354,6 +378,7 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     // ---- normalise, transpose through LDS (the ring is free once every wave is past its last fragment read) and store
     // whole 16-byte pieces: lane holds query qb*32 + lq of its sub-tile, channels b*32 + 8*(r/4) + 4*half + r%4
     constexpr int OP = HD * 2 + 8;                 // row pitch of the staging rows: 8-byte writes of 32 lanes hit 64 banks
+    __builtin_amdgcn_s_waitcnt(FA_WAIT_VM);        // (the zero fills of tiles past the end have landed too)
     fenced_barrier();
     unsigned char* stage = ring + wave * (FA_QW * OP);
 #pragma unroll
