@@ -15,18 +15,21 @@
 // of lane half h then holds key 16*(r/8) + 8*h + r%8 of the 32-key block, so registers 8*s2 .. 8*s2+7 are eight
 // CONSECUTIVE keys - exactly one 16-byte read of a V^T row for the second MFMA, whose contraction index they become.
 //
-// Keys are walked in blocks of 32 inside tiles of 64.  Tiles travel global -> LDS directly (global_load_lds, 16 bytes
-// per lane) into a ring of four slots; the 16-byte chunks of a row are XOR-swizzled on the global-address side so the
-// fragment reads are free of bank conflicts.  One barrier per tile.
+// Keys are walked in blocks of 32 inside tiles of 64.  Tiles travel global -> LDS directly (buffer loads that write
+// LDS, 16 bytes per lane) into a ring of four slots; the 16-byte chunks of a row are XOR-swizzled on the global-address
+// side so the fragment reads are free of bank conflicts.  One barrier per tile; the loads of the tile after next are
+// spread over the slots of the tile's first step.
 //
 // Software pipeline over blocks j: while the vector ALUs turn S_j into probabilities P_j, the matrix pipe computes
-// S_{j+1} and O += V_{j-1} P_{j-1}.  No MFMA of a step depends on a vector result of the same step.
+// S_{j+1} and O += V_{j-1} P_{j-1}.  No MFMA of a step depends on a vector result of the same step.  Q sits in AGPRs and
+// feeds the first MFMA directly, S is produced in VGPRs (those MFMAs are written out as instructions: at one wave per
+// SIMD the compiler would keep every accumulator in AGPRs and copy), O accumulates in AGPRs.
 //
 // Softmax: statistics and accumulators are fp32, probabilities are rounded to bf16 for the second MFMA.  The exponent
-// reference m of a query is moved only when a score outgrows it by more than FA_SLACK (base-2 units): any reference
-// gives the same quotient O / l, a stale one merely bounds the probabilities by 2^FA_SLACK instead of 1, and O is
-// rescaled on a rare wave-uniform side path instead of on every block.  On the usual path a lane never needs the
-// other lane half.
+// reference m of a query is fixed before the key loop, on its first 32 scores: any reference gives the same quotient
+// O / l, a stale one merely lets probabilities exceed 1.  Each step only notes whether a block of probabilities summed
+// to more than 16 * 2^FA_SLACK; a workgroup in which that happened runs once more with the exact row maxima as
+// references.  On the usual path a lane never needs the other lane half and O is never rescaled.
 #include <type_traits>
 
 #include "common.h"
@@ -38,7 +41,7 @@ constexpr int FA_BK = 64;         // keys per tile (two blocks of 32)
 constexpr int FA_QW = 64;         // queries per wave
 constexpr int FA_THREADS = 256;
 constexpr int FA_SLOTS = 4;
-constexpr float FA_SLACK = 8.0f;  // how far (base 2) a score may outgrow the exponent reference before O is rescaled
+constexpr float FA_SLACK = 8.0f;  // how far (base 2) scores may outgrow the exponent reference before the workgroup repeats
 
 #define FA_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 constexpr int FA_WAIT_VM = 0x0F70;      // s_waitcnt vmcnt(0), other counters untouched (gfx9 encoding)
