@@ -42,7 +42,7 @@ void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, in
 void launch_fill_u8(uint8_t* p, uint8_t v, int64_t n, hipStream_t s);
 
 // ---- simple tiled GEMM on the vector ALUs (kernels_gemm_simple.hip) ------------------------------
-enum EpiKind { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_ADD_RESID = 2, EPI_SWIGLU = 3 };
+enum EpiKind { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_ADD_RESID = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4 };
 // C[M,N] = A[M,K] * W[N,K]^T, fp32 accumulate.  A and W are `dtype`.
 //   EPI_STORE     : out [M][N] in dtype
 //   EPI_STORE_F32 : out [M][N] float
@@ -63,6 +63,14 @@ void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi
 // Same contract; K % 32 == 0; EPI_SWIGLU needs N % 64 == 0.
 constexpr int GEMM_SKINNY_MAX_M = 64;
 void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout = 0);
+// The q/k/v projection of a decode step with the rotary embedding and the KV-cache append in its epilogue:
+// W = [Wq; Wk; Wv] ((hq + 2 hkv) * hd rows), qkv [M][(hq + 2 hkv) * hd] receives rotated q and k and plain v; row m's
+// rotated key and its value also go to row cache_row[m] of kcache / vcache ([cache rows][hkv * hd]).  pos, cache_row:
+// device, [M]; cs: cos/sin table [position][hd / 2].  Needs hd % 32 == 0 and M <= GEMM_SKINNY_MAX_M.
+bool gemm_skinny_qkv_rope_supported(int M, int hd);
+void launch_gemm_skinny_qkv_rope(const void* A, const void* W, int M, int K, void* qkv, const int32_t* pos, const float2* cs,
+                                 const int32_t* cache_row, void* kcache, void* vcache, int hq, int hkv, int hd, hipStream_t s,
+                                 int layout = 0);
 
 // ---- attention ------------------------------------------------------------------------------------
 // One wave per (query row, query head), online softmax over keys 0..npos[row].

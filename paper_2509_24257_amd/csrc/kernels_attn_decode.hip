@@ -1,6 +1,8 @@
 // Attention of the token-by-token path (Section 5.5): one query position per live sequence against that sequence's
-// KV cache.  One workgroup (8 waves) per (query row, KV head); the G = Hq / Hkv query heads that share the KV head are
-// processed together, so every cached key and value is read once.
+// KV cache.  One workgroup (8 waves) per (query row, G query heads that share one KV head).  With many rows G is the
+// whole group Hq / Hkv, so every cached key and value is read once; with few rows (a step of 8 sequences gives only 64
+// such workgroups, and the score and value arithmetic of four heads in one wave is what the step then waits for) the
+// group is split over several workgroups, which re-read the keys and values through the L2 they share.
 //
 //   keys    : walked 64 at a time, block kb by wave kb % 8.  A key row (head_dim bf16) is read by head_dim/8 adjacent
 //             lanes, 16 bytes each, so a load instruction covers whole rows; each lane multiplies its 8 channels with
@@ -18,6 +20,7 @@ namespace vl {
 
 constexpr int AD_THREADS = 512;
 constexpr int AD_WAVES = 8;
+constexpr int AD_FILL = 256;                                   // workgroups wanted: one per compute unit
 
 // DPL consecutive bf16 channels of one value row, held as loaded
 template <int DPL> struct VLoad;
@@ -38,7 +41,7 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
                                                                  const bf16* __restrict__ k, const bf16* __restrict__ v,
                                                                  int64_t kv_stride, const int32_t* __restrict__ kv_row0,
                                                                  const int32_t* __restrict__ npos, bf16* __restrict__ out,
-                                                                 int hq, float scale, bool out_tiled) {
+                                                                 int hq, int kv_group, float scale, bool out_tiled) {
     constexpr int LPK = HD / 8;                                 // lanes per key row
     constexpr int KPP = WAVE / LPK;                             // keys per pass
     constexpr int DPL = HD / WAVE;                              // value channels per lane
@@ -47,7 +50,8 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
     __shared__ float part_o[AD_WAVES][G][HD];
     __shared__ float part_m[AD_WAVES][G], part_l[AD_WAVES][G];
     const int64_t row = blockIdx.x;
-    const int kvh = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int qh0 = blockIdx.y * G, kvh = qh0 / kv_group;      // first query head of this workgroup, its KV head
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nkeys = npos[row] + 1;
     const int64_t base = (int64_t)kv_row0[row];
     const int sub = lane % LPK, kin = lane / LPK;               // 16-byte piece of a row, key within a pass
@@ -55,7 +59,7 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
     float qr[G][8];                                             // this lane's 8 channels of every query head, pre-scaled
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const bf16x8 t = *(const bf16x8*)(q + row * q_stride + (int64_t)(kvh * G + g) * HD + sub * 8);
+        const bf16x8 t = *(const bf16x8*)(q + row * q_stride + (int64_t)(qh0 + g) * HD + sub * 8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) qr[g][i] = (float)t[i] * scale;
     }
@@ -164,7 +168,7 @@ __global__ __launch_bounds__(AD_THREADS) void attn_decode_kernel(const bf16* __r
             num = fmaf(part_o[w][g][d], f, num);
             den = fmaf(part_l[w][g], f, den);
         }
-        const int col = (kvh * G + g) * HD + d;
+        const int col = (qh0 + g) * HD + d;
         out[out_tiled ? tiled_off(row, col, (int64_t)hq * HD) : row * (int64_t)hq * HD + col] = (bf16)(num / den);
     }
 }
@@ -178,11 +182,11 @@ template <int G>
 static void launch_g(const bf16* q, int64_t q_stride, const bf16* k, const bf16* v, int64_t kv_stride, const int32_t* kv_row0,
                      const int32_t* npos, bf16* out, int64_t rows, int hq, int hkv, int hd, hipStream_t s, bool out_tiled) {
     const float scale = 1.0f / sqrtf((float)hd);
-    dim3 grid((unsigned)rows, (unsigned)hkv);
+    dim3 grid((unsigned)rows, (unsigned)(hq / G));
     if (hd == 64)
-        attn_decode_kernel<G, 64><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale, out_tiled);
+        attn_decode_kernel<G, 64><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, hq / hkv, scale, out_tiled);
     else
-        attn_decode_kernel<G, 128><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, scale, out_tiled);
+        attn_decode_kernel<G, 128><<<grid, AD_THREADS, 0, s>>>(q, q_stride, k, v, kv_stride, kv_row0, npos, out, hq, hq / hkv, scale, out_tiled);
 }
 
 void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const void* v, int64_t kv_stride,
@@ -190,7 +194,9 @@ void launch_attn_decode(const void* q, int64_t q_stride, const void* k, const vo
                         hipStream_t s, bool out_tiled) {
     if (rows <= 0) return;
     const bf16 *qq = (const bf16*)q, *kk = (const bf16*)k, *vv = (const bf16*)v;
-    switch (hq / hkv) {
+    int g = hq / hkv;                                           // heads per workgroup: halve until the grid covers the chip
+    while (g > 1 && rows * (hq / g) < AD_FILL) g >>= 1;
+    switch (g) {
         case 1: launch_g<1>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;
         case 2: launch_g<2>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;
         case 4: launch_g<4>(qq, q_stride, kk, vv, kv_stride, kv_row0, npos, (bf16*)out, rows, hq, hkv, hd, s, out_tiled); break;

@@ -13,6 +13,9 @@
 //               bytes of every W row
 //   epilogues : as in the large-tile kernel; for SwiGLU the two row groups are the gate rows and the up rows of the
 //               same 16 channels (W interleaves 32 gate rows, 32 up rows), so silu(gate) * up is formed in place.
+//               For the q/k/v projection of a decode step the two row groups are 16 channels of a head and their
+//               rotary partners half a head further on: the epilogue rounds to bf16, rotates query and key pairs by
+//               the row's position and appends keys and values to the KV cache, which saves the step a launch per layer.
 #include "common.h"
 #include "kernels.h"
 
@@ -20,11 +23,25 @@ namespace vl {
 
 constexpr int GS_THREADS = 512;
 constexpr int GS_WAVES = 8;
+#ifndef GS_UNROLL
+#define GS_UNROLL 4
+#endif
+
+// what the rotary epilogue needs: positions and cache rows per row of A, the cos/sin table [position][hd/2], the caches
+struct RopeArgs {
+    const int32_t* pos;
+    const int32_t* cache_row;
+    const float2* cs;
+    bf16 *kc, *vc;
+    int hq, hkv, hd;
+};
 
 template <int EPI, int MT, int NG>
 __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
-                                                                 int M, int N, int K, void* __restrict__ outp, int layout) {
+                                                                 int M, int N, int K, void* __restrict__ outp, int layout,
+                                                                 RopeArgs ra) {
     static_assert(EPI != EPI_SWIGLU || NG == 2, "SwiGLU pairs a gate group with an up group");
+    static_assert(EPI != EPI_QKV_ROPE || NG == 2, "the rotary epilogue pairs a group of channels with its partners");
     __shared__ __align__(16) float red[GS_WAVES][NG * MT * 256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int fr = lane & 15, fq = lane >> 4;
@@ -34,6 +51,12 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
         r0 = b * 64 + h * 16;
         r1 = r0 + 32;
         ch0 = b * 32 + h * 16;
+    } else if (EPI == EPI_QKV_ROPE) {
+        const int half = ra.hd >> 1, bph = half >> 4;           // 16-channel blocks per half head
+        const int head = blockIdx.x / bph;
+        ch0 = (blockIdx.x - head * bph) * 16;                   // first channel within the head
+        r0 = head * ra.hd + ch0;
+        r1 = r0 + half;
     } else {
         r0 = blockIdx.x * (16 * NG);
         r1 = r0 + 16;
@@ -60,32 +83,58 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
     const int steps = K >> 5;                                   // k-steps of 32
     int ks = (int)(((int64_t)steps * wave) / GS_WAVES);
     const int ke = (int)(((int64_t)steps * (wave + 1)) / GS_WAVES);
-    for (; ks + 4 <= ke; ks += 4) {
-        bf16x8 a0[4], a1[4], b[MT][4];
+    // two register stages of U k-steps each: the loads of one stage are in flight while the other feeds the MFMAs, so a
+    // wave never sits out a whole memory round trip between two bursts of loads
+    constexpr int U = GS_UNROLL;
+    bf16x8 a0[2][U], a1[2][U], b[2][MT][U];
+    auto load_stage = [&](int st, int k0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t ow = (ks + u) * w_step, oa = (ks + u) * a_step;
-            a0[u] = *(const bf16x8*)(w0 + ow);
-            if (NG == 2) a1[u] = *(const bf16x8*)(w1 + ow);
+        for (int u = 0; u < U; ++u) {
+            const int64_t ow = (k0 + u) * w_step, oa = (k0 + u) * a_step;
+            a0[st][u] = *(const bf16x8*)(w0 + ow);
+            if (NG == 2) a1[st][u] = *(const bf16x8*)(w1 + ow);
 #pragma unroll
-            for (int t = 0; t < MT; ++t) b[t][u] = *(const bf16x8*)(ap[t] + oa);
+            for (int t = 0; t < MT; ++t) b[st][t][u] = *(const bf16x8*)(ap[t] + oa);
         }
+    };
+    auto mma_stage = [&](int st) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], b[t][u], acc[0][t], 0, 0, 0);
-                if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], b[t][u], acc[NG - 1][t], 0, 0, 0);
+                acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[st][u], b[st][t][u], acc[0][t], 0, 0, 0);
+                if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[st][u], b[st][t][u], acc[NG - 1][t], 0, 0, 0);
             }
+    };
+    const int n_it = (ke - ks) / U;
+    if (n_it > 0) load_stage(0, ks);
+    int it = 0;
+    for (; it + 2 < n_it; it += 2) {                            // branch-free body: the wait counts stay exact
+        load_stage(1, ks + (it + 1) * U);
+        __builtin_amdgcn_sched_barrier(0);                      // keep the loads ahead of the MFMAs they overlap
+        mma_stage(0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_stage(0, ks + (it + 2) * U);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_stage(1);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    if (n_it - it == 2) {                                       // wave-uniform
+        load_stage(1, ks + (it + 1) * U);
+        mma_stage(0);
+        mma_stage(1);
+    } else if (n_it - it == 1) {
+        mma_stage(0);
+    }
+    ks += n_it * U;
     for (; ks < ke; ++ks) {
         const int64_t ow = ks * w_step, oa = ks * a_step;
-        const bf16x8 a0 = *(const bf16x8*)(w0 + ow), a1 = *(const bf16x8*)((NG == 2 ? w1 : w0) + ow);
+        const bf16x8 wa = *(const bf16x8*)(w0 + ow), wb = *(const bf16x8*)((NG == 2 ? w1 : w0) + ow);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            const bf16x8 b = *(const bf16x8*)(ap[t] + oa);
-            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, b, acc[0][t], 0, 0, 0);
-            if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b, acc[NG - 1][t], 0, 0, 0);
+            const bf16x8 bb = *(const bf16x8*)(ap[t] + oa);
+            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, bb, acc[0][t], 0, 0, 0);
+            if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, bb, acc[NG - 1][t], 0, 0, 0);
         }
     }
 #pragma unroll
@@ -110,6 +159,36 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
             if (m < M && f < F)
                 ((bf16*)outp)[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
         }
+    } else if (EPI == EPI_QKV_ROPE) {
+        const int half = ra.hd >> 1, head = r0 / ra.hd;
+        const int64_t kvd = (int64_t)ra.hkv * ra.hd;
+        for (int e = threadIdx.x; e < PER_GROUP; e += GS_THREADS) {
+            float x1 = 0.f, x2 = 0.f;
+#pragma unroll
+            for (int w = 0; w < GS_WAVES; ++w) {
+                x1 += red[w][e];
+                x2 += red[w][PER_GROUP + e];
+            }
+            const int l = (e & 255) >> 2, r = e & 3;
+            const int m = (e >> 8) * 16 + (l & 15), c = ch0 + 4 * (l >> 4) + r;
+            if (m >= M) continue;
+            bf16 y1 = (bf16)x1, y2 = (bf16)x2;                  // the projection's own rounding comes first
+            if (head < ra.hq + ra.hkv) {
+                const float2 t = ra.cs[(int64_t)ra.pos[m] * half + c];
+                const float f1 = (float)y1, f2 = (float)y2;
+                y1 = (bf16)(f1 * t.x - f2 * t.y);
+                y2 = (bf16)(f2 * t.x + f1 * t.y);
+            }
+            bf16* o = (bf16*)outp + (int64_t)m * N + r0 + 4 * (l >> 4) + r;
+            o[0] = y1;
+            o[half] = y2;
+            if (head >= ra.hq) {
+                const bool is_k = head < ra.hq + ra.hkv;
+                bf16* d = (is_k ? ra.kc : ra.vc) + (int64_t)ra.cache_row[m] * kvd + (head - ra.hq - (is_k ? 0 : ra.hkv)) * ra.hd + c;
+                d[0] = y1;
+                d[half] = y2;
+            }
+        }
     } else {
         for (int e = threadIdx.x; e < NG * PER_GROUP; e += GS_THREADS) {
             float v = 0.f;
@@ -131,9 +210,10 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
 template <int EPI, int NG>
 static void launch_mt(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s, int layout) {
     const unsigned grid = (unsigned)((N + 16 * NG - 1) / (16 * NG));
-    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout);
-    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout);
-    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout);
+    const RopeArgs none{};
+    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none);
+    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none);
+    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none);
 }
 
 // one row group per workgroup while two would leave fewer than two workgroups per compute unit
@@ -153,6 +233,21 @@ void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int e
         case EPI_ADD_RESID: launch_ng<EPI_ADD_RESID>(a, w, M, N, K, out, s, layout); break;
         default: launch_ng<EPI_SWIGLU>(a, w, M, N, K, out, s, layout); break;
     }
+}
+
+bool gemm_skinny_qkv_rope_supported(int M, int hd) { return M <= GEMM_SKINNY_MAX_M && (hd & 31) == 0; }
+
+void launch_gemm_skinny_qkv_rope(const void* A, const void* W, int M, int K, void* qkv, const int32_t* pos, const float2* cs,
+                                 const int32_t* cache_row, void* kcache, void* vcache, int hq, int hkv, int hd, hipStream_t s,
+                                 int layout) {
+    if (M <= 0) return;
+    const int N = (hq + 2 * hkv) * hd;
+    const RopeArgs ra{pos, cache_row, cs, (bf16*)kcache, (bf16*)vcache, hq, hkv, hd};
+    const unsigned grid = (unsigned)(N / 32);                   // a workgroup owns 16 channels and their 16 partners
+    const bf16 *a = (const bf16*)A, *w = (const bf16*)W;
+    if (M <= 16) gemm_skinny_kernel<EPI_QKV_ROPE, 1, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra);
+    else if (M <= 32) gemm_skinny_kernel<EPI_QKV_ROPE, 2, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra);
+    else gemm_skinny_kernel<EPI_QKV_ROPE, 4, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra);
 }
 
 }  // namespace vl

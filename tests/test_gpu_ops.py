@@ -332,6 +332,36 @@ def test_decode_attention_matches_oracle(hq, hkv, hd):
         ctx.close()
 
 
+@pytest.mark.parametrize("hq,hkv,hd,rows", [(32, 8, 128, 64), (8, 1, 128, 256), (4, 2, 64, 128), (8, 2, 128, 70)])
+def test_decode_attention_many_rows(hq, hkv, hd, rows):
+    """With enough query rows one workgroup serves all (or half of) the query heads of a KV head; with few rows, as in the
+    test above, every query head has a workgroup of its own.  Rows read overlapping windows of one cache."""
+    say(f"decode attention hq={hq} hkv={hkv} hd={hd} rows={rows}")
+    m = synth.small_model("bf16", n_layers=1, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, d_model=256)
+    ctx = P.Context(H.c_cfg(m, 1024, 512, 256), 0, 0)
+    try:
+        rng = np.random.default_rng(rows * 1000 + hq * 100 + hkv * 10 + hd)
+        cache_rows, kvd = 450, hkv * hd
+        n_keys = rng.integers(1, 260, size=rows)
+        n_keys[:4] = [1, 64, 65, 259]
+        first = rng.integers(0, cache_rows - n_keys + 1)
+        k_bits = synth.f32_to_bf16_bits((rng.standard_normal((cache_rows, kvd)) * 1.5).astype(np.float32))
+        v_bits = synth.f32_to_bf16_bits(rng.standard_normal((cache_rows, kvd)).astype(np.float32))
+        q_bits = synth.f32_to_bf16_bits((rng.standard_normal((rows, hq * hd)) * 1.5).astype(np.float32))
+        d_q, d_k, d_v = H.to_dev(q_bits), H.to_dev(k_bits), H.to_dev(v_bits)
+        d_o = torch.zeros((rows, hq * hd), dtype=torch.int16, device=H.DEV)
+        ctx.vl_op_attention_decode_bf16(d_q.data_ptr(), d_k.data_ptr(), d_v.data_ptr(), cache_rows, first.tolist(), n_keys.tolist(),
+                                        d_o.data_ptr())
+        got = O.upcast(H.bits_from_dev(d_o)).reshape(rows, hq, hd)
+        kf, vf, qf = O.upcast(k_bits), O.upcast(v_bits), O.upcast(q_bits)
+        for r, (f0, t) in enumerate(zip(first.tolist(), n_keys.tolist())):
+            ref = O.causal_attention(qf[r].reshape(1, hq, hd), kf[f0:f0 + t].reshape(t, hkv, hd), vf[f0:f0 + t].reshape(t, hkv, hd),
+                                     np.array([t - 1]))[0]
+            np.testing.assert_allclose(got[r], ref, rtol=2 ** -8, atol=2e-3)
+    finally:
+        ctx.close()
+
+
 # ------------------------------------------------------------------ Merkle commitment (Section 5.6 / 5.7)
 @pytest.mark.parametrize("d,dtype", [(256, "f32"), (256, "bf16"), (64, "f32"), (200, "bf16"), (4096, "bf16"), (8192, "f32"),
                                      (1000, "f32"), (16384, "bf16"), (264, "f32"), (72, "bf16"), (8200, "f32"), (8, "f32")])
