@@ -362,14 +362,21 @@ void block_decode(vl_ctx* c, int l, int rows, const int32_t* pos, const int32_t*
     const LayerW w = layer_w(c, l);
     hipStream_t s = c->stream;
     const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
-    launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16);
-    if (c->bf16 && gemm_skinny_qkv_rope_supported(rows, m.head_dim)) {
-        launch_gemm_skinny_qkv_rope(c->xn, w.wqkv, rows, m.d_model, c->qkv, pos, c->rope_cs, cache_row, c->kcache + lo, c->vcache + lo,
-                                    m.n_q_heads, m.n_kv_heads, m.head_dim, s, GL_A_TILED | GL_W_TILED);
+    // few rows: the first RMSNorm runs inside the projection that consumes it
+    const bool fuse_norm = c->bf16 && gemm_skinny_norm_supported(rows, m.d_model) && gemm_skinny_qkv_rope_supported(rows, m.head_dim);
+    if (fuse_norm) {
+        launch_gemm_skinny_qkv_rope(c->resid, w.wqkv, rows, m.d_model, c->qkv, pos, c->rope_cs, cache_row, c->kcache + lo, c->vcache + lo,
+                                    m.n_q_heads, m.n_kv_heads, m.head_dim, s, GL_W_TILED, (const float*)w.attn_norm, m.rms_eps);
     } else {
-        gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
-        launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s, c->kcache + lo, c->vcache + lo,
-                    cache_row);
+        launch_rmsnorm(c->resid, w.attn_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16);
+        if (c->bf16 && gemm_skinny_qkv_rope_supported(rows, m.head_dim)) {
+            launch_gemm_skinny_qkv_rope(c->xn, w.wqkv, rows, m.d_model, c->qkv, pos, c->rope_cs, cache_row, c->kcache + lo,
+                                        c->vcache + lo, m.n_q_heads, m.n_kv_heads, m.head_dim, s, GL_A_TILED | GL_W_TILED);
+        } else {
+            gemm(c, c->xn, w.wqkv, rows, (int)p.qkv_w, m.d_model, EPI_STORE, c->qkv);
+            launch_rope(c->qkv, m.dtype, pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s, c->kcache + lo, c->vcache + lo,
+                        cache_row);
+        }
     }
     if (c->bf16 && attn_decode_supported(m.n_q_heads, m.n_kv_heads, m.head_dim))
         launch_attn_decode(c->qkv, p.qkv_w, c->kcache + lo, c->vcache + lo, p.kvd, cache_row0, pos, c->attn, rows, m.n_q_heads,

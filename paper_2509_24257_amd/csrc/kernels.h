@@ -67,10 +67,13 @@ void launch_gemm_skinny(const void* A, const void* W, int M, int N, int K, int e
 // W = [Wq; Wk; Wv] ((hq + 2 hkv) * hd rows), qkv [M][(hq + 2 hkv) * hd] receives rotated q and k and plain v; row m's
 // rotated key and its value also go to row cache_row[m] of kcache / vcache ([cache rows][hkv * hd]).  pos, cache_row:
 // device, [M]; cs: cos/sin table [position][hd / 2].  Needs hd % 32 == 0 and M <= GEMM_SKINNY_MAX_M.
+// With norm_gain != NULL, A is instead the fp32 residual [M][K] (row-major) and the kernel applies RMSNorm(gain, eps)
+// to it first (allowed when gemm_skinny_norm_supported(M, K)).
 bool gemm_skinny_qkv_rope_supported(int M, int hd);
 void launch_gemm_skinny_qkv_rope(const void* A, const void* W, int M, int K, void* qkv, const int32_t* pos, const float2* cs,
                                  const int32_t* cache_row, void* kcache, void* vcache, int hq, int hkv, int hd, hipStream_t s,
-                                 int layout = 0);
+                                 int layout = 0, const float* norm_gain = nullptr, float eps = 0.f);
+bool gemm_skinny_norm_supported(int M, int K);
 
 // ---- attention ------------------------------------------------------------------------------------
 // One wave per (query row, query head), online softmax over keys 0..npos[row].

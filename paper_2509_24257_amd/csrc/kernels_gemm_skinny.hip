@@ -16,6 +16,12 @@
 //               For the q/k/v projection of a decode step the two row groups are 16 channels of a head and their
 //               rotary partners half a head further on: the epilogue rounds to bf16, rotates query and key pairs by
 //               the row's position and appends keys and values to the KV cache, which saves the step a launch per layer.
+//   RMSNorm   : with XS > 0 the operand A is the fp32 residual stream: every workgroup first normalises the (<= 16) rows
+//               into LDS as bf16, one wave per row with the sums taken in the order of the stand-alone kernel, while its
+//               first weight loads are in flight, and then reads the A fragments from there.  The rows come out of L2;
+//               this replaces a launch whose whole cost was its latency.  Used for the q/k/v projection, whose grid is
+//               one workgroup per compute unit; for the gate/up projection (3.5 workgroups per compute unit, each
+//               repeating the rows' two round trips) it measured 4 us slower than the separate kernel.
 #include "common.h"
 #include "kernels.h"
 
@@ -36,13 +42,25 @@ struct RopeArgs {
     int hq, hkv, hd;
 };
 
-template <int EPI, int MT, int NG>
+struct NormArgs {
+    const float* gain;
+    float eps;
+};
+// bytes of LDS for the normalised rows: row pitch 2 K + 16 (the 16 spread the rows of a fragment read over the banks)
+constexpr int GS_XS = 8 * (2 * 4096 + 16);                   // 8 rows of 4096 channels
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+template <int EPI, int MT, int NG, int XS = 0>
 __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                                                                  int M, int N, int K, void* __restrict__ outp, int layout,
-                                                                 RopeArgs ra) {
+                                                                 RopeArgs ra, NormArgs na) {
+    static_assert(XS == 0 || MT == 1, "the fused RMSNorm holds at most 16 rows");
+    __shared__ __align__(16) unsigned char xs[XS > 0 ? XS : 16];
     static_assert(EPI != EPI_SWIGLU || NG == 2, "SwiGLU pairs a gate group with an up group");
     static_assert(EPI != EPI_QKV_ROPE || NG == 2, "the rotary epilogue pairs a group of channels with its partners");
-    __shared__ __align__(16) float red[GS_WAVES][NG * MT * 256];
+    // partial tiles of the eight waves; with XS > 0 they reuse the rows' LDS once the main loop is done with it
+    __shared__ __align__(16) float red_own[XS > 0 ? 1 : GS_WAVES][NG * MT * 256];
+    static_assert(XS == 0 || XS >= (int)sizeof(float) * GS_WAVES * NG * MT * 256, "the rows' buffer also holds the partial tiles");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int fr = lane & 15, fq = lane >> 4;
     int r0, r1, ch0 = 0;                                        // first W row of each group; first output channel (SwiGLU)
@@ -68,6 +86,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
     const bf16* w0 = W + (wt ? tiled_off(wr0, 0, K) : (int64_t)wr0 * K) + fq * 8;
     const bf16* w1 = W + (wt ? tiled_off(wr1, 0, K) : (int64_t)wr1 * K) + fq * 8;
     const bf16* ap[MT];
+    const int x_pitch = 2 * K + 16, x_off = min(fr, M - 1) * x_pitch + fq * 16;     // XS > 0: byte offsets into xs
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         const int ar = min(t * 16 + fr, M - 1);
@@ -87,17 +106,32 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
     // wave never sits out a whole memory round trip between two bursts of loads
     constexpr int U = GS_UNROLL;
     bf16x8 a0[2][U], a1[2][U], b[2][MT][U];
-    auto load_stage = [&](int st, int k0) {
+    auto load_w = [&](int st, int k0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t ow = (k0 + u) * w_step, oa = (k0 + u) * a_step;
+            const int64_t ow = (k0 + u) * w_step;
             a0[st][u] = *(const bf16x8*)(w0 + ow);
             if (NG == 2) a1[st][u] = *(const bf16x8*)(w1 + ow);
-#pragma unroll
-            for (int t = 0; t < MT; ++t) b[st][t][u] = *(const bf16x8*)(ap[t] + oa);
         }
     };
-    auto mma_stage = [&](int st) {
+    // A fragments: from memory they travel with the weights of their stage; from LDS (XS > 0) they are read when the
+    // stage is used, which keeps the kernel at two workgroups per compute unit
+    auto load_b = [&](int st, int k0) {
+        if (XS > 0) return;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < MT; ++t) b[st][t][u] = *(const bf16x8*)(ap[t] + (k0 + u) * a_step);
+    };
+    auto load_stage = [&](int st, int k0) {
+        load_w(st, k0);
+        load_b(st, k0);
+    };
+    auto mma_stage = [&](int st, int k0) {
+        if (XS > 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) b[st][0][u] = *(const bf16x8*)(xs + x_off + (k0 + u) * 64);
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -107,24 +141,69 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
             }
     };
     const int n_it = (ke - ks) / U;
-    if (n_it > 0) load_stage(0, ks);
+    if (n_it > 0) load_w(0, ks);
+    if (XS > 0) {
+        __builtin_amdgcn_sched_barrier(0);                      // the weight loads above go out first
+        const int k4 = K >> 2;
+        const float4* g4 = (const float4*)na.gain;
+        // the row is wave-uniform and said to be: addresses are then a scalar base plus one per-lane offset
+        for (int row = __builtin_amdgcn_readfirstlane(wave); row < M; row += GS_WAVES) {
+            const float4* xr = (const float4*)((const float*)A + (int64_t)row * K);
+            // K / 4 is a multiple of 64, so a whole wave is inside or outside the row together; the loads of a batch go out
+            // back to back (a chunk past the end re-reads the last one and is not used)
+            float ss = 0.f;
+            constexpr int PB = 16;                              // loads per batch: a row of 4096 is one batch
+            for (int c0 = 0; c0 < k4; c0 += WAVE * PB) {       // c0 and every condition on it are wave-uniform
+                float4 v[PB];
+#pragma unroll
+                for (int j = 0; j < PB; ++j) v[j] = (xr + min(c0 + WAVE * j, k4 - WAVE))[lane];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < PB; ++j)
+                    if (c0 + WAVE * j < k4) ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+            }
+            ss = wave_sum(ss);
+            const float r = 1.0f / sqrtf(ss / (float)K + na.eps);
+            for (int c0 = 0; c0 < k4; c0 += WAVE * PB) {
+                float4 v[PB], g[PB];
+#pragma unroll
+                for (int j = 0; j < PB; ++j) {
+                    const int i = min(c0 + WAVE * j, k4 - WAVE);
+                    v[j] = (xr + i)[lane];
+                    g[j] = (g4 + i)[lane];
+                }
+#pragma unroll
+                for (int j = 0; j < PB; ++j)                     // all loads of the batch are issued here, none inside a branch below
+                    asm volatile("" : "+v"(v[j].x), "+v"(v[j].y), "+v"(v[j].z), "+v"(v[j].w), "+v"(g[j].x), "+v"(g[j].y), "+v"(g[j].z),
+                                 "+v"(g[j].w));
+#pragma unroll
+                for (int j = 0; j < PB; ++j)
+                    if (c0 + WAVE * j < k4)
+                        *(bf16x4*)(xs + row * x_pitch + (c0 + WAVE * j + lane) * 8) =
+                            bf16x4{(bf16)(v[j].x * r * g[j].x), (bf16)(v[j].y * r * g[j].y), (bf16)(v[j].z * r * g[j].z),
+                                   (bf16)(v[j].w * r * g[j].w)};
+            }
+        }
+        __syncthreads();
+    }
+    if (n_it > 0) load_b(0, ks);
     int it = 0;
     for (; it + 2 < n_it; it += 2) {                            // branch-free body: the wait counts stay exact
         load_stage(1, ks + (it + 1) * U);
         __builtin_amdgcn_sched_barrier(0);                      // keep the loads ahead of the MFMAs they overlap
-        mma_stage(0);
+        mma_stage(0, ks + it * U);
         __builtin_amdgcn_sched_barrier(0);
         load_stage(0, ks + (it + 2) * U);
         __builtin_amdgcn_sched_barrier(0);
-        mma_stage(1);
+        mma_stage(1, ks + (it + 1) * U);
         __builtin_amdgcn_sched_barrier(0);
     }
     if (n_it - it == 2) {                                       // wave-uniform
         load_stage(1, ks + (it + 1) * U);
-        mma_stage(0);
-        mma_stage(1);
+        mma_stage(0, ks + it * U);
+        mma_stage(1, ks + (it + 1) * U);
     } else if (n_it - it == 1) {
-        mma_stage(0);
+        mma_stage(0, ks + it * U);
     }
     ks += n_it * U;
     for (; ks < ke; ++ks) {
@@ -132,11 +211,13 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
         const bf16x8 wa = *(const bf16x8*)(w0 + ow), wb = *(const bf16x8*)((NG == 2 ? w1 : w0) + ow);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            const bf16x8 bb = *(const bf16x8*)(ap[t] + oa);
+            const bf16x8 bb = XS > 0 ? *(const bf16x8*)(xs + x_off + ks * 64) : *(const bf16x8*)(ap[t] + oa);
             acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, bb, acc[0][t], 0, 0, 0);
             if (NG == 2) acc[NG - 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, bb, acc[NG - 1][t], 0, 0, 0);
         }
     }
+    float (*red)[NG * MT * 256] = XS > 0 ? (float (*)[NG * MT * 256]) xs : red_own;
+    if (XS > 0) __syncthreads();                                // every wave has read its last fragment from xs
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
@@ -211,10 +292,13 @@ template <int EPI, int NG>
 static void launch_mt(const bf16* A, const bf16* W, int M, int N, int K, void* out, hipStream_t s, int layout) {
     const unsigned grid = (unsigned)((N + 16 * NG - 1) / (16 * NG));
     const RopeArgs none{};
-    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none);
-    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none);
-    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none);
+    const NormArgs plain{};
+    if (M <= 16) gemm_skinny_kernel<EPI, 1, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none, plain);
+    else if (M <= 32) gemm_skinny_kernel<EPI, 2, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none, plain);
+    else gemm_skinny_kernel<EPI, 4, NG><<<grid, GS_THREADS, 0, s>>>(A, W, M, N, K, out, layout, none, plain);
 }
+
+bool gemm_skinny_norm_supported(int M, int K) { return M >= 1 && M <= 16 && (K & 255) == 0 && (int64_t)M * (2 * K + 16) <= GS_XS; }
 
 // one row group per workgroup while two would leave fewer than two workgroups per compute unit
 template <int EPI>
@@ -239,15 +323,22 @@ bool gemm_skinny_qkv_rope_supported(int M, int hd) { return M <= GEMM_SKINNY_MAX
 
 void launch_gemm_skinny_qkv_rope(const void* A, const void* W, int M, int K, void* qkv, const int32_t* pos, const float2* cs,
                                  const int32_t* cache_row, void* kcache, void* vcache, int hq, int hkv, int hd, hipStream_t s,
-                                 int layout) {
+                                 int layout, const float* norm_gain, float eps) {
     if (M <= 0) return;
     const int N = (hq + 2 * hkv) * hd;
     const RopeArgs ra{pos, cache_row, cs, (bf16*)kcache, (bf16*)vcache, hq, hkv, hd};
+    if (norm_gain) {
+        // A = fp32 rows that the kernel normalises itself (see the header)
+        gemm_skinny_kernel<EPI_QKV_ROPE, 1, 2, GS_XS><<<(unsigned)(N / 32), GS_THREADS, 0, s>>>((const bf16*)A, (const bf16*)W, M, N, K, qkv,
+                                                                                              layout, ra, NormArgs{norm_gain, eps});
+        return;
+    }
+    const NormArgs plain{};
     const unsigned grid = (unsigned)(N / 32);                   // a workgroup owns 16 channels and their 16 partners
     const bf16 *a = (const bf16*)A, *w = (const bf16*)W;
-    if (M <= 16) gemm_skinny_kernel<EPI_QKV_ROPE, 1, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra);
-    else if (M <= 32) gemm_skinny_kernel<EPI_QKV_ROPE, 2, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra);
-    else gemm_skinny_kernel<EPI_QKV_ROPE, 4, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra);
+    if (M <= 16) gemm_skinny_kernel<EPI_QKV_ROPE, 1, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra, plain);
+    else if (M <= 32) gemm_skinny_kernel<EPI_QKV_ROPE, 2, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra, plain);
+    else gemm_skinny_kernel<EPI_QKV_ROPE, 4, 2><<<grid, GS_THREADS, 0, s>>>(a, w, M, N, K, qkv, layout, ra, plain);
 }
 
 }  // namespace vl
