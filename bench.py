@@ -42,9 +42,9 @@ def attention_flops(model, lengths):
 # figure belongs to one version of the kernel source: any edit of that file makes it unknown again.
 GATEUP_TRAFFIC = {
     "source": "paper_2509_24257_amd/csrc/kernels_gemm_mfma.hip",
-    "sha256": "4837cc5abfd6c1a3ad7ead4822233b9752f763540580e4d91c0621fd01d47b74",
+    "sha256": "55b35760216e3eddb1689943381ce7bdb4eb9cbb44e4b879b001c5856f5e9603",
     "workload": "cfg1-8b-b8x1024",
-    "bytes_per_launch": (1376380 / 0.500 + 229376 / 1.000) * 1024,
+    "bytes_per_launch": (1376506 / 0.500 + 229376 / 1.000) * 1024,
 }
 
 
@@ -212,7 +212,9 @@ def main():
     gu_tflops = gu_flops / (gu_avg_ms * 1e-3) / 1e12 if gu_launches else 0.0
     compare_bytes = c * n * m.d_model * (4 + (2 if bf else 4))
     compare_gbs = compare_bytes / (stages.get("compare", 0) * 1e-3) / 1e9 if stages.get("compare") else None
-    argmax_gbs = n * m.vocab * 4 / (stages.get("argmax", 0) * 1e-3) / 1e9 if stages.get("argmax") else None
+    # the argmax over the vocabulary is the epilogue of the LM-head GEMM (no logits in memory); the "argmax" stage is
+    # the reduction of its per-part maxima: vocab / 128 (value, index) pairs per token
+    argmax_gbs = n * ((m.vocab + 127) // 128) * 8 / (stages.get("argmax", 0) * 1e-3) / 1e9 if stages.get("argmax") else None
 
     out = {
         "metric": "verified tokens/s (8B-shape bf16 prefill+compare, 1 GPU); MFMA util %",

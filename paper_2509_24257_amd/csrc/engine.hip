@@ -167,6 +167,7 @@ struct vl_ctx {
 
     int64_t last_n = 0;
     bool last_has_logits = false;
+    int64_t logits_rows = 0;                                // rows of the most recent call whose logits are in `logits`
 
     // optional per-stage timing (vl_profile_enable): event pairs recorded around launches, read after the sync
     struct Span { int stage; hipEvent_t a, b; };
@@ -394,6 +395,43 @@ void lm_head_logits(vl_ctx* c, int rows) {
     const vl_model_cfg& m = c->cfg;
     { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, c->final_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, c->stream, c->bf16); }
     { StageSpan sp(c, VL_STAGE_LM_GEMM); gemm(c, c->xn, c->lm_head, rows, m.vocab, m.d_model, EPI_STORE_F32, c->logits); }
+    c->logits_rows = rows;
+}
+
+// Final norm, LM head, argmax and token check of `rows` rows.  With more rows than the weight-streaming GEMM takes, the
+// argmax is the epilogue of the LM-head GEMM and the logits are never written (their buffer holds the per-part maxima;
+// vl_get_logits recomputes them on demand from the normalised rows, which stay in xn).
+// ea / eb (optional) are recorded around the argmax part.
+int lm_head_argmax(vl_ctx* c, int rows, const int32_t* committed, float margin, float* gap, uint8_t* tok_ok, hipEvent_t ea = nullptr,
+                   hipEvent_t eb = nullptr) {
+    const vl_model_cfg& m = c->cfg;
+    hipStream_t s = c->stream;
+    const int64_t ld = rows, parts = argmax_parts(m.vocab);
+    const bool fused = c->bf16 && rows > GEMM_SKINNY_MAX_M && (parts * ld * 8 + ld * 4) <= c->plan.N * c->plan.V * 4;
+    if (!fused) {
+        lm_head_logits(c, rows);
+        if (ea) HIP_TRY(c, hipEventRecord(ea, s));
+        {
+            StageSpan sp(c, VL_STAGE_ARGMAX);
+            launch_argmax(c->logits, rows, m.vocab, committed, margin, c->argmax, gap, tok_ok, s);
+        }
+        if (eb) HIP_TRY(c, hipEventRecord(eb, s));
+        return VL_OK;
+    }
+    { StageSpan sp(c, VL_STAGE_NORM); launch_rmsnorm(c->resid, c->final_norm, c->xn, m.dtype, rows, m.d_model, m.rms_eps, s, c->bf16); }
+    ArgmaxParts ap{c->logits, (int32_t*)c->logits + parts * ld, committed, c->logits + 2 * parts * ld, ld};
+    {
+        StageSpan sp(c, VL_STAGE_LM_GEMM);
+        launch_gemm_mfma_argmax(c->xn, c->lm_head, rows, m.vocab, m.d_model, ap, s, GL_A_TILED | GL_W_TILED);
+    }
+    if (ea) HIP_TRY(c, hipEventRecord(ea, s));
+    {
+        StageSpan sp(c, VL_STAGE_ARGMAX);
+        launch_argmax_reduce(ap, rows, m.vocab, committed, margin, c->argmax, gap, tok_ok, s);
+    }
+    if (eb) HIP_TRY(c, hipEventRecord(eb, s));
+    c->logits_rows = 0;
+    return VL_OK;
 }
 
 int check_batch(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_t B, const int32_t* commit_layers, int32_t C,
@@ -510,15 +548,10 @@ int run_prefill(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, int32_
         }
     }
     if (run_head) {
-        lm_head_logits(c, rows);
         hipEvent_t a = c->events[ev++], b = c->events[ev++];
-        HIP_TRY(c, hipEventRecord(a, s));
-        {
-            StageSpan sp(c, VL_STAGE_ARGMAX);
-            launch_argmax(c->logits, n, m.vocab, verify ? committed_argmax : nullptr, verify ? tol->logit_margin : 0.f, c->argmax, c->gap,
-                          verify ? c->tok_ok : nullptr, s);
-        }
-        HIP_TRY(c, hipEventRecord(b, s));
+        const int hrc = lm_head_argmax(c, rows, verify ? committed_argmax : nullptr, verify ? tol->logit_margin : 0.f, c->gap,
+                                       verify ? c->tok_ok : nullptr, a, b);
+        if (hrc) return hrc;
         cmp_spans.push_back({a, b});
         if (!verify && out_argmax) HIP_TRY(c, hipMemcpyAsync(out_argmax, c->argmax, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
     }
@@ -896,8 +929,7 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
             emit(l, (int)np, d_src);
         }
         if (out_argmax) {
-            lm_head_logits(c, (int)np);
-            launch_argmax(c->logits, np, m.vocab, nullptr, 0.f, c->argmax, nullptr, nullptr, s);
+            lm_head_argmax(c, (int)np, nullptr, 0.f, nullptr, nullptr);
             launch_scatter_i32(c->argmax, out_argmax, d_src, np, s);
         }
     }
@@ -914,8 +946,7 @@ int vl_decode_commit(vl_ctx* c, const int32_t* tokens, const int32_t* lengths, c
             emit(l, rows, cur_src);
         }
         if (out_argmax) {
-            lm_head_logits(c, rows);
-            launch_argmax(c->logits, rows, m.vocab, nullptr, 0.f, c->argmax, nullptr, nullptr, s);
+            lm_head_argmax(c, rows, nullptr, 0.f, nullptr, nullptr);
             launch_scatter_i32(c->argmax, out_argmax, cur_src, rows, s);
         }
     };
@@ -968,6 +999,11 @@ int vl_get_logits(vl_ctx* c, int64_t tok_begin, int64_t tok_end, float* out) {
     if (!out) return c->fail(VL_E_ARG, "out is NULL");
     HIP_TRY(c, hipSetDevice(c->device));
     const int64_t v = c->cfg.vocab;
+    if (c->logits_rows < c->last_n) {                          // the call fused the argmax into the LM head: materialise them now
+        gemm(c, c->xn, c->lm_head, (int)c->last_n, c->cfg.vocab, c->cfg.d_model, EPI_STORE_F32, c->logits);
+        HIP_TRY(c, hipGetLastError());
+        c->logits_rows = c->last_n;
+    }
     HIP_TRY(c, hipMemcpyAsync(out, c->logits + tok_begin * v, (size_t)((tok_end - tok_begin) * v * 4), hipMemcpyDeviceToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return VL_OK;

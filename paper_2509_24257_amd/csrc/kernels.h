@@ -42,7 +42,7 @@ void launch_scatter_i32(const int32_t* src, int32_t* out, const int32_t* dst, in
 void launch_fill_u8(uint8_t* p, uint8_t v, int64_t n, hipStream_t s);
 
 // ---- simple tiled GEMM on the vector ALUs (kernels_gemm_simple.hip) ------------------------------
-enum EpiKind { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_ADD_RESID = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4 };
+enum EpiKind { EPI_STORE = 0, EPI_STORE_F32 = 1, EPI_ADD_RESID = 2, EPI_SWIGLU = 3, EPI_QKV_ROPE = 4, EPI_ARGMAX = 5 };
 // C[M,N] = A[M,K] * W[N,K]^T, fp32 accumulate.  A and W are `dtype`.
 //   EPI_STORE     : out [M][N] in dtype
 //   EPI_STORE_F32 : out [M][N] float
@@ -58,6 +58,24 @@ void launch_gemm_simple(const void* A, const void* W, int dtype, int M, int N, i
 // layout: bit 0 = A is a tiled image, bit 1 = W is, bit 2 = the SwiGLU output is written as one (see tiled_off).
 enum GemmLayout { GL_A_TILED = 1, GL_W_TILED = 2, GL_OUT_TILED = 4 };
 void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout = 0);
+
+// LM head with the argmax in the epilogue: the logits never reach memory.  The GEMM runs transposed (rows = vocabulary,
+// columns = tokens), so that a lane's accumulators are 64 vocabulary entries of ONE token and the maximum over them needs
+// no cross-lane work; every wave reduces its 128 x 64 block to one (maximum, lowest index attaining it) per token.
+//   pmax, pidx : [parts][ld], parts = ceil(vocab / 128); part p covers vocabulary rows 128 p .. 128 p + 127
+//   tok, ztok  : tok[n] (may be NULL) is a vocabulary index per token whose logit is also wanted: ztok[n] receives it
+//                (entries with tok[n] outside [0, vocab) are left untouched)
+struct ArgmaxParts {
+    float* pmax;
+    int32_t* pidx;
+    const int32_t* tok;
+    float* ztok;
+    int64_t ld;
+};
+inline int argmax_parts(int vocab) { return (vocab + 127) / 128; }
+// Wlm [vocab][K] and X [tokens][K] as for launch_gemm_mfma's W and A (layout bits GL_W_TILED / GL_A_TILED)
+void launch_gemm_mfma_argmax(const void* X, const void* Wlm, int tokens, int vocab, int K, const ArgmaxParts& parts, hipStream_t s,
+                             int layout = 0);
 
 // ---- bf16 weight-streaming GEMM for M <= 64 rows (kernels_gemm_skinny.hip) --------------------------
 // Same contract; K % 32 == 0; EPI_SWIGLU needs N % 64 == 0.
@@ -109,6 +127,9 @@ void launch_compare(const float* h_hat, const void* committed, int hidden_dtype,
                     const vl_bit_rule* rule = nullptr, vl_bit_stats* bit_stats = nullptr);
 void launch_argmax(const float* logits, int64_t rows, int vocab, const int32_t* committed, float margin,
                    int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s);
+// The same outputs from the per-part maxima of launch_gemm_mfma_argmax (parts.tok must have been `committed`).
+void launch_argmax_reduce(const ArgmaxParts& parts, int64_t rows, int vocab, const int32_t* committed, float margin,
+                          int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s);
 // ---- Merkle commitment (kernels_merkle.hip) -----------------------------------------------------------
 // roots[r][32] = SHA-256 Merkle root over the d canonical-float32 scalars of states row r (dtype VL_F32 / VL_BF16);
 // d <= 16384.

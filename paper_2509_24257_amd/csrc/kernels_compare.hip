@@ -217,6 +217,47 @@ void launch_argmax(const float* logits, int64_t rows, int vocab, const int32_t* 
     argmax_kernel<<<dim3((unsigned)rows), 256, 0, s>>>(logits, vocab, committed, margin, out_argmax, out_gap, out_ok);
 }
 
+// The same decision from per-part maxima: 16 tokens x 16 slices of the parts per workgroup; (maximum, lowest index) is a
+// total order, so the result does not depend on how the parts are grouped.
+__global__ __launch_bounds__(256) void argmax_reduce_kernel(ArgmaxParts ap, int n_parts, int64_t rows, int vocab,
+                                                            const int32_t* __restrict__ committed, float margin,
+                                                            int32_t* __restrict__ out_argmax, float* __restrict__ out_gap,
+                                                            uint8_t* __restrict__ out_ok) {
+    __shared__ float sv[16][16];
+    __shared__ int si[16][16];
+    const int t = threadIdx.x & 15, slice = threadIdx.x >> 4;
+    const int64_t row = (int64_t)blockIdx.x * 16 + t;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    if (row < rows)
+        for (int p = slice; p < n_parts; p += 16) take_better(bv, bi, ap.pmax[p * ap.ld + row], ap.pidx[p * ap.ld + row]);
+    sv[slice][t] = bv;
+    si[slice][t] = bi;
+    __syncthreads();
+    if (slice != 0 || row >= rows) return;
+#pragma unroll
+    for (int w = 1; w < 16; ++w) take_better(bv, bi, sv[w][t], si[w][t]);
+    if (bi == 0x7fffffff) bi = 0;                              // every logit NaN
+    float gap = 0.f;
+    uint8_t ok = 1;
+    if (committed) {
+        const int c = committed[row];
+        if (c == -1) { gap = 0.f; ok = 1; }
+        else if (c < 0 || c >= vocab) { gap = INFINITY; ok = 0; }
+        else { gap = bv - ap.ztok[row]; ok = (gap <= margin); }     // NaN compares false -> reject
+    }
+    if (out_argmax) out_argmax[row] = bi;
+    if (out_gap) out_gap[row] = gap;
+    if (out_ok) out_ok[row] = ok;
+}
+
+void launch_argmax_reduce(const ArgmaxParts& parts, int64_t rows, int vocab, const int32_t* committed, float margin,
+                          int32_t* out_argmax, float* out_gap, uint8_t* out_ok, hipStream_t s) {
+    if (rows <= 0) return;
+    argmax_reduce_kernel<<<dim3((unsigned)((rows + 15) / 16)), 256, 0, s>>>(parts, argmax_parts(vocab), rows, vocab, committed, margin,
+                                                                           out_argmax, out_gap, out_ok);
+}
+
 // ---------------------------------------------------------------- flags + summary: one workgroup, fixed order
 __global__ __launch_bounds__(1024) void finalize_kernel(const uint8_t* __restrict__ hid_ok, const uint8_t* __restrict__ tok_ok,
                                                         const vl_tok_stats* __restrict__ stats, int C, int64_t rows,

@@ -29,7 +29,9 @@
 //
 // Epilogues: store as bf16 / store as fp32 / add into the fp32 residual stream / SwiGLU on interleaved gate|up
 // column blocks (W rows alternate 32 gate rows and 32 up rows, so MFMA block j=0 is gate and j=1 is up of the same
-// 32 channels and the product silu(gate)*up never leaves registers).
+// 32 channels and the product silu(gate)*up never leaves registers) / column-wise argmax (the LM head run with the
+// vocabulary as rows: a lane's 64 accumulators of a column are 64 logits of one token, so each wave reduces its
+// 128 x 64 block to a maximum and its lowest index per token in registers, plus one exchange between the lane halves).
 #include <algorithm>
 
 #include "common.h"
@@ -57,7 +59,7 @@ constexpr int GM_WAIT_VM0_LGKM0 = 0x0070;                       // vmcnt(0)  lgk
 template <int EPI>
 __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __restrict__ A, const bf16* __restrict__ W,
                                                                   int M, int N, int K, void* __restrict__ outp,
-                                                                  int tiles_m, int tiles_n, int layout) {
+                                                                  int tiles_m, int tiles_n, int layout, ArgmaxParts ap) {
     __shared__ __align__(1024) unsigned char ring[GM_SLOTS * GM_SLOT];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -197,7 +199,39 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 
         // ---- epilogue of tile (cm0, cn0).  Lane l of a 32x32 block holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4.
         const bool interior = (cm0 + GM_BM <= M) && (cn0 + GM_BN <= N);    // uniform: no per-element guards needed
-        if (interior) {
+        if (EPI == EPI_ARGMAX) {
+            const int part = (cm0 >> 7) + grp;                  // this wave's 128 rows
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = cn0 + wn * 64 + j * 32 + col_in;
+                const int want = (ap.tok && col < N) ? ap.tok[col] : -1;
+                float bv = -INFINITY, zt = 0.f;
+                int bi = 0x7fffffff;
+                bool hit = false;
+                // rows in ascending order within the lane: strict '>' keeps the lowest index among equals; NaN never wins
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = cm0 + grp * 128 + i * 32 + (r >> 2) * 8 + row_half + (r & 3);
+                        const float v = acc[i][j][r];
+                        if (row < M) {
+                            if (v > bv) { bv = v; bi = row; }
+                            if (row == want) { zt = v; hit = true; }
+                        }
+                    }
+                const float ov = __shfl_xor(bv, 32, WAVE);      // the other half of the rows
+                const int oi = __shfl_xor(bi, 32, WAVE);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                if (col < N && cm0 + grp * 128 < M) {           // (a wave whose rows all lie past the matrix has no part)
+                    if (lane < 32) {
+                        ap.pmax[part * ap.ld + col] = bv;
+                        ap.pidx[part * ap.ld + col] = bi;
+                    }
+                    if (hit) ap.ztok[col] = zt;
+                }
+            }
+        } else if (interior) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int mb = cm0 + grp * 128 + i * 32 + row_half;
@@ -296,7 +330,7 @@ static void launch_one(const bf16* A, const bf16* W, int M, int N, int K, void* 
     const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (N + GM_BN - 1) / GM_BN;
     const int total = tiles_m * tiles_n;
     const int grid = std::min(((total + GM_XCDS - 1) / GM_XCDS) * GM_XCDS, resident_workgroups());
-    gemm_mfma_kernel<EPI><<<dim3((unsigned)grid), GM_THREADS, 0, s>>>(A, W, M, N, K, out, tiles_m, tiles_n, layout);
+    gemm_mfma_kernel<EPI><<<dim3((unsigned)grid), GM_THREADS, 0, s>>>(A, W, M, N, K, out, tiles_m, tiles_n, layout, ArgmaxParts{});
 }
 
 void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi, void* out, hipStream_t s, int layout) {
@@ -309,6 +343,19 @@ void launch_gemm_mfma(const void* A, const void* W, int M, int N, int K, int epi
         case EPI_ADD_RESID: launch_one<EPI_ADD_RESID>(a, w, M, N, K, out, s, layout); break;
         default: launch_one<EPI_SWIGLU>(a, w, M, N, K, out, s, layout); break;
     }
+}
+
+void launch_gemm_mfma_argmax(const void* X, const void* Wlm, int tokens, int vocab, int K, const ArgmaxParts& parts, hipStream_t s,
+                             int layout) {
+    if (tokens <= 0 || vocab <= 0) return;
+    // transposed: the vocabulary is the row operand, the tokens are the column operand
+    const int M = vocab, N = tokens;
+    const int lay = ((layout & GL_W_TILED) ? GL_A_TILED : 0) | ((layout & GL_A_TILED) ? GL_W_TILED : 0);
+    const int tiles_m = (M + GM_BM - 1) / GM_BM, tiles_n = (N + GM_BN - 1) / GM_BN;
+    const int total = tiles_m * tiles_n;
+    const int grid = std::min(((total + GM_XCDS - 1) / GM_XCDS) * GM_XCDS, resident_workgroups());
+    gemm_mfma_kernel<EPI_ARGMAX><<<dim3((unsigned)grid), GM_THREADS, 0, s>>>((const bf16*)Wlm, (const bf16*)X, M, N, K, nullptr, tiles_m,
+                                                                             tiles_n, lay, parts);
 }
 
 }  // namespace vl

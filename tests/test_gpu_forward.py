@@ -74,6 +74,11 @@ def check_verify_against_oracle(ctx, om, wl, x, committed_f32, z, tol_hidden, to
         clear = (srt[:, -1] - srt[:, -2]) >= tie_gap
         np.testing.assert_array_equal(a_gpu[clear], ref["argmax"][clear])
         assert np.abs(gap_gpu - ref["gap"]).max() <= 2 * tol_logit
+        # with many rows the argmax is taken inside the LM-head GEMM and the logits above were produced afterwards, on
+        # demand, by the storing GEMM: the two must describe the same numbers, ties (lowest index) included
+        np.testing.assert_array_equal(a_gpu, O.argmax_lowest(zg))
+        live = np.flatnonzero(cam_t >= 0)
+        np.testing.assert_array_equal(gap_gpu[live], zg.max(axis=1)[live] - zg[live, cam_t[live]])
     assert sm["ms_forward"] > 0 and 0 <= sm["ms_compare"] <= sm["ms_forward"]
     return flags, stats, sm
 
