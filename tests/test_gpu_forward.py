@@ -219,6 +219,39 @@ def test_small_bf16_decode_commit_both_forms(small_bf16):
     assert st_again.tobytes() == st_d.tobytes()
 
 
+@pytest.mark.parametrize("hq,hkv,hd", [(4, 2, 64), (8, 2, 128)])
+def test_bf16_decode_commit_many_sequences(hq, hkv, hd):
+    """44 sequences of different lengths decoded token by token: the number of live rows falls from 44 through 32 and 16
+    to 1, so the decode step runs with every row-tile count of the weight-streaming GEMM (its rotary + cache-append
+    epilogue included), with the RMSNorm inside the q/k/v projection (<= 16 rows) and outside it."""
+    say(f"bf16 decode_commit with 44 sequences, hq={hq} hkv={hkv} hd={hd}")
+    m = synth.small_model("bf16", n_layers=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, d_model=256, random_gains=True)
+    rng = np.random.default_rng(hq + hd)
+    lengths = [int(t) for t in rng.integers(2, 40, size=44)]
+    lengths[5] = 1
+    wl = synth.small_workload(m, lengths, [1, 2], seed=11)
+    ctx = H.make_ctx(m, 2048, 48, 64)
+    try:
+        om = H.oracle_model(m)
+        x = synth.tokens(wl)
+        hid, z, _ = oracle_commitments(om, wl, x)
+        val_d, st_d, amax_d = H.run_commit(ctx, wl, x, "decode", prompt_lens=None)
+        val_p, st_p, amax_p = H.run_commit(ctx, wl, x, "decode", prompt_lens=wl.prompt_lens)
+        val_f, _, _ = H.run_commit(ctx, wl, x, "prefill")
+        for c, l in enumerate(wl.commit_layers):
+            assert H.rel_l2_rows(val_d[c], hid[l]).max() <= 2e-2
+            assert H.rel_l2_rows(val_p[c], hid[l]).max() <= 2e-2
+            assert max(H.rel_l2_rows(val_d[c], val_f[c]).max(), H.rel_l2_rows(val_p[c], val_f[c]).max()) <= wl.tol_rel_l2 / 2
+        srt = np.sort(z, axis=1)
+        clear = (srt[:, -1] - srt[:, -2]) >= 0.1
+        np.testing.assert_array_equal(amax_d[clear], O.argmax_lowest(z)[clear])
+        np.testing.assert_array_equal(amax_p[clear], O.argmax_lowest(z)[clear])
+        flags, _, sm = H.run_verify(ctx, wl, x, st_d, amax_d)
+        assert flags.all() and sm["n_rejected"] == 0
+    finally:
+        ctx.close()
+
+
 def test_small_bf16_results_are_bit_reproducible_and_batch_independent(small_bf16):
     ctx, om, wl, x = small_bf16
     say("small bf16 determinism")
