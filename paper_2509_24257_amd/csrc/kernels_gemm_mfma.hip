@@ -244,7 +244,7 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const float g = acc[i][0][r], u = acc[i][1][r];
-                        out[(int64_t)((r >> 2) * 8 + (r & 3)) * rs] = (bf16)(g / (1.0f + __expf(-g)) * u);
+                        out[(int64_t)((r >> 2) * 8 + (r & 3)) * rs] = (bf16)silu_mul(g, u);
                     }
                 } else {
 #pragma unroll
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(GM_THREADS, 1) void gemm_mfma_kernel(const bf16* __
                             const int m = mb + (r >> 2) * 8 + (r & 3);
                             if (m < M) {
                                 const float g = acc[i][0][r], u = acc[i][1][r];
-                                out[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
+                                out[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)silu_mul(g, u);
                             }
                         }
                     }

@@ -238,7 +238,7 @@ __global__ __launch_bounds__(GS_THREADS) void gemm_skinny_kernel(const bf16* __r
             const int l = (e & 255) >> 2, r = e & 3;
             const int m = (e >> 8) * 16 + (l & 15), f = ch0 + 4 * (l >> 4) + r;
             if (m < M && f < F)
-                ((bf16*)outp)[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)(g / (1.0f + __expf(-g)) * u);
+                ((bf16*)outp)[(layout & GL_OUT_TILED) ? tiled_off(m, f, F) : (int64_t)m * F + f] = (bf16)silu_mul(g, u);
         }
     } else if (EPI == EPI_QKV_ROPE) {
         const int half = ra.hd >> 1, head = r0 / ra.hd;
