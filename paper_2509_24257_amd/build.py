@@ -39,10 +39,29 @@ def _compile(src: str) -> str:
     return obj
 
 
+def _check_hand_issued_mfma() -> None:
+    """The attention kernel issues some matrix instructions as inline assembly; the compiler then inserts none of the
+    wait states they need next to vector instructions.  Its device assembly is generated once more as text and checked
+    (see check_mfma_asm.py); a violation fails the build instead of giving wrong numbers now and then."""
+    if HERE not in sys.path:
+        sys.path.insert(0, HERE)
+    import check_mfma_asm                                       # sits beside this file; also when run as a script
+    asm = os.path.join(OBJ_DIR, "kernels_attn_mfma.s")
+    cmd = [hipcc()] + FLAGS + ["-S", "--cuda-device-only", os.path.join(CSRC, "kernels_attn_mfma.hip"), "-o", asm]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc -S failed for kernels_attn_mfma.hip:\n%s\n%s" % (r.stdout, r.stderr))
+    bad = check_mfma_asm.check(asm)
+    if bad:
+        raise RuntimeError("hand-issued MFMA next to a vector instruction on its registers:\n" + "\n".join(bad[:20]))
+
+
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        chk = ex.submit(_check_hand_issued_mfma)
         objs = list(ex.map(_compile, SOURCES))
+        chk.result()
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", "-o", LIB] + objs   # unresolved symbols fail the build, not the load
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
