@@ -336,16 +336,14 @@ void block_prefill(vl_ctx* c, int l, const BatchIdx& bi, const int32_t* cache_ro
     {
         StageSpan sp(c, VL_STAGE_ROPE);
         const int64_t lo = (int64_t)l * p.N * p.kvd * p.esz;
-        // bf16: only the keys are rotated here; the attention kernel rotates the queries as it loads them
         launch_rope(c->qkv, m.dtype, bi.pos, c->rope_cs, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, s,
-                    cache_row ? c->kcache + lo : nullptr, cache_row ? c->vcache + lo : nullptr, cache_row, c->bf16);
+                    cache_row ? c->kcache + lo : nullptr, cache_row ? c->vcache + lo : nullptr, cache_row);
         if (c->bf16) launch_transpose_v(c->qkv, c->vt, bi.vt_col, rows, m.n_q_heads, m.n_kv_heads, m.head_dim, p.vt_ld, s);
     }
     {
         StageSpan sp(c, VL_STAGE_ATTENTION);
         if (c->bf16) {
-            launch_attn_mfma(c->qkv, rows, c->vt, p.vt_ld, bi.tiles, bi.n_tiles, c->attn, m.n_q_heads, m.n_kv_heads, m.head_dim, s, true,
-                             c->rope_cs);
+            launch_attn_mfma(c->qkv, rows, c->vt, p.vt_ld, bi.tiles, bi.n_tiles, c->attn, m.n_q_heads, m.n_kv_heads, m.head_dim, s, true);
         } else {
             const char* q = c->qkv;
             launch_attn_rowwise(q, p.qkv_w, q + p.qd * p.esz, q + (p.qd + p.kvd) * p.esz, p.qkv_w, bi.seq_row0, bi.pos, c->attn,

@@ -25,10 +25,8 @@ void launch_retile(const void* src, void* dst, int64_t rows, int K, int64_t row0
 // Rotate query and key heads of qkv [rows][(hq+2hkv)*hd] in place using the cos/sin table
 // cs[pos][hd/2] (float2 = cos, sin).  With cache_row != NULL the rotated keys and the values of row n are also
 // copied to row cache_row[n] of kcache / vcache ([cache rows][hkv*hd], same dtype).
-// keys_only: leave the query heads as they are (the matrix-core attention kernel rotates them itself).
 void launch_rope(void* qkv, int dtype, const int32_t* pos, const float2* cs, int64_t rows, int hq, int hkv,
-                 int hd, hipStream_t s, void* kcache = nullptr, void* vcache = nullptr, const int32_t* cache_row = nullptr,
-                 bool keys_only = false);
+                 int hd, hipStream_t s, void* kcache = nullptr, void* vcache = nullptr, const int32_t* cache_row = nullptr);
 // vt[g][c][ vt_col[n] ] = V head g, channel c of token n (bf16); ldv = row pitch of vt in elements.
 void launch_transpose_v(const void* qkv, void* vt, const int32_t* vt_col, int64_t rows, int hq, int hkv, int hd,
                         int64_t ldv, hipStream_t s);
@@ -120,10 +118,8 @@ struct AttnTile { int32_t q_row0, q_rows, kv_row0, kv_len, vt_col0, pos0; };  //
 int attn_mfma_q_span(int hq, int hkv);
 // The kernel addresses a sequence's keys with 32-bit byte offsets: the longest sequence it can take.
 bool attn_mfma_fits(int hq, int hkv, int hd, int64_t max_seq_len);
-// rope_cs != NULL: the queries in qkv are NOT yet rotated; the kernel applies the rotary embedding to them on load
-// (table cs[position][hd/2] as for launch_rope; the keys must already be rotated).
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
-                      void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled = false, const float2* rope_cs = nullptr);
+                      void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled = false);
 
 // ---- compare / argmax / flags (kernels_compare.hip) ------------------------------------------------
 void launch_compare(const float* h_hat, const void* committed, int hidden_dtype, int64_t rows, int d, float tol_rel,

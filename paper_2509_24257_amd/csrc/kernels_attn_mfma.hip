@@ -57,7 +57,7 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
                                                                const bf16* __restrict__ vt, int64_t ldv,
                                                                const AttnTile* __restrict__ tiles,
                                                                bf16* __restrict__ out, int hq, int hkv, float scale_log2e,
-                                                               bool out_tiled, const float2* __restrict__ rope_cs) {
+                                                               bool out_tiled) {
 #if defined(__HIP_DEVICE_COMPILE__)     // the host pass needs the launch stub only; the body uses device-only types
     constexpr int KSTEPS = HD / 16;               // MFMA k-steps over the head dimension
     constexpr int DB = HD / 32;                   // 32-channel output blocks
@@ -95,34 +95,6 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
         const bf16* qp = qkv + (int64_t)(t.q_row0 + q_idx) * pitch + (int64_t)head * HD + half * 8;
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) qf[qb][s] = *(const bf16x8*)(qp + s * 16);
-    }
-    // The rotary embedding of the queries, if asked for (rope_cs = cos/sin table [position][HD/2]): a lane's fragment of
-    // k-step s and the one of k-step s + KSTEPS/2 hold the two partners of eight rotary pairs, so the rotation is
-    // lane-local; same expressions and roundings as the row kernel that rotates the keys.  This saves that kernel
-    // reading and writing every query head (four fifths of its traffic at 32 query / 8 KV heads).
-    if (rope_cs) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float2* tab = rope_cs + (int64_t)q_pos[qb] * (HD / 2) + half * 8;
-#pragma unroll
-            for (int s = 0; s < KSTEPS / 2; ++s) {
-                const float4* t4 = (const float4*)(tab + s * 16);          // 8 x (cos, sin) = 64 bytes
-                float4 cs4[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) cs4[j] = t4[j];
-                const bf16x8 x1 = qf[qb][s], x2 = qf[qb][s + KSTEPS / 2];
-                bf16x8 y1, y2;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float cj = (j & 1) ? cs4[j >> 1].z : cs4[j >> 1].x, sj = (j & 1) ? cs4[j >> 1].w : cs4[j >> 1].y;
-                    const float f1 = (float)x1[j], f2 = (float)x2[j];
-                    y1[j] = (bf16)(f1 * cj - f2 * sj);
-                    y2[j] = (bf16)(f2 * cj + f1 * sj);
-                }
-                qf[qb][s] = y1;
-                qf[qb][s + KSTEPS / 2] = y2;
-            }
-        }
     }
     const int wave_first_pos = t.pos0 + qs * FA_QW;
 
@@ -466,12 +438,12 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
 
 template <int HD>
 static void launch_hd(const bf16* qkv, int64_t n_rows, const bf16* vt, int64_t ldv, const AttnTile* tiles, int n_tiles, bf16* out,
-                      int hq, int hkv, float scale_log2e, bool out_tiled, const float2* rope_cs, hipStream_t s) {
+                      int hq, int hkv, float scale_log2e, bool out_tiled, hipStream_t s) {
     const int hpw = attn_mfma_heads_per_wg(hq, hkv);
     const unsigned grid = (unsigned)n_tiles * (unsigned)(hq / hpw);
-    if (hpw == 4) attn_mfma_kernel<HD, 4><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled, rope_cs);
-    else if (hpw == 2) attn_mfma_kernel<HD, 2><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled, rope_cs);
-    else attn_mfma_kernel<HD, 1><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled, rope_cs);
+    if (hpw == 4) attn_mfma_kernel<HD, 4><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
+    else if (hpw == 2) attn_mfma_kernel<HD, 2><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
+    else attn_mfma_kernel<HD, 1><<<grid, FA_THREADS, 0, s>>>(qkv, n_rows, vt, ldv, tiles, out, hq, hkv, scale_log2e, out_tiled);
 }
 
 bool attn_mfma_fits(int hq, int hkv, int hd, int64_t max_seq_len) {
@@ -479,11 +451,11 @@ bool attn_mfma_fits(int hq, int hkv, int hd, int64_t max_seq_len) {
 }
 
 void launch_attn_mfma(const void* qkv, int64_t n_rows, const void* vt, int64_t ldv, const AttnTile* tiles, int n_tiles,
-                      void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled, const float2* rope_cs) {
+                      void* out, int hq, int hkv, int hd, hipStream_t s, bool out_tiled) {
     if (n_tiles <= 0) return;
     const float scale_log2e = (1.0f / sqrtf((float)hd)) * 1.4426950408889634f;
-    if (hd == 128) launch_hd<128>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, n_tiles, (bf16*)out, hq, hkv, scale_log2e, out_tiled, rope_cs, s);
-    else launch_hd<64>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, n_tiles, (bf16*)out, hq, hkv, scale_log2e, out_tiled, rope_cs, s);
+    if (hd == 128) launch_hd<128>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, n_tiles, (bf16*)out, hq, hkv, scale_log2e, out_tiled, s);
+    else launch_hd<64>((const bf16*)qkv, n_rows, (const bf16*)vt, ldv, tiles, n_tiles, (bf16*)out, hq, hkv, scale_log2e, out_tiled, s);
 }
 
 }  // namespace vl

@@ -159,16 +159,16 @@ template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void rope_kernel(T* __restrict__ qkv, const int32_t* __restrict__ pos,
                                                             const float2* __restrict__ cs, int hq, int hkv, int hd,
                                                             T* __restrict__ kc, T* __restrict__ vc,
-                                                            const int32_t* __restrict__ cache_row, int h0) {
+                                                            const int32_t* __restrict__ cache_row) {
     const int64_t n = blockIdx.x;
     const int half = hd >> 1;
     const int p = pos[n];
     T* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd;
     const float2* tab = cs + (int64_t)p * half;
-    const int pairs = (hq + hkv - h0) * half;      // query heads then key heads are contiguous in the row; heads < h0 are skipped
+    const int pairs = (hq + hkv) * half;           // query heads then key heads are contiguous in the row
     const int64_t dst = cache_row ? (int64_t)cache_row[n] * hkv * hd : 0;
     for (int i = threadIdx.x; i < pairs; i += ROW_THREADS) {
-        const int h = h0 + i / half, c = i - (h - h0) * half;
+        const int h = i / half, c = i - h * half;
         const float2 t = tab[c];
         T* a = row + h * hd + c;
         const float x1 = to_f32(a[0]), x2 = to_f32(a[half]);
@@ -191,16 +191,16 @@ __global__ __launch_bounds__(ROW_THREADS) void rope_kernel(T* __restrict__ qkv, 
 __global__ __launch_bounds__(ROW_THREADS) void rope_vec_kernel(bf16* __restrict__ qkv, const int32_t* __restrict__ pos,
                                                                 const float2* __restrict__ cs, int hq, int hkv, int hd,
                                                                 bf16* __restrict__ kc, bf16* __restrict__ vc,
-                                                                const int32_t* __restrict__ cache_row, int h0) {
+                                                                const int32_t* __restrict__ cache_row) {
     const int64_t n = blockIdx.x;
     const int half = hd >> 1, vph = half >> 3;     // vectors per half head
     const int p = pos[n];
     bf16* row = qkv + n * (int64_t)(hq + 2 * hkv) * hd;
     const float2* tab = cs + (int64_t)p * half;
-    const int items = (hq + hkv - h0) * vph;       // heads < h0 are skipped
+    const int items = (hq + hkv) * vph;
     const int64_t dst = cache_row ? (int64_t)cache_row[n] * hkv * hd : 0;
     for (int i = threadIdx.x; i < items; i += ROW_THREADS) {
-        const int h = h0 + i / vph, c = (i - (h - h0) * vph) * 8;
+        const int h = i / vph, c = (i - h * vph) * 8;
         bf16* a = row + h * hd + c;
         const bf16x8 x1 = *(const bf16x8*)a, x2 = *(const bf16x8*)(a + half);
         bf16x8 y1, y2;
@@ -226,18 +226,17 @@ __global__ __launch_bounds__(ROW_THREADS) void rope_vec_kernel(bf16* __restrict_
 }
 
 void launch_rope(void* qkv, int dtype, const int32_t* pos, const float2* cs, int64_t rows, int hq, int hkv, int hd,
-                 hipStream_t s, void* kcache, void* vcache, const int32_t* cache_row, bool keys_only) {
+                 hipStream_t s, void* kcache, void* vcache, const int32_t* cache_row) {
     if (rows <= 0) return;
-    const int h0 = keys_only ? hq : 0;
     if (dtype == VL_BF16 && (hd & 15) == 0)
         rope_vec_kernel<<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((bf16*)qkv, pos, cs, hq, hkv, hd, (bf16*)kcache, (bf16*)vcache,
-                                                                     cache_row, h0);
+                                                                     cache_row);
     else if (dtype == VL_BF16)
         rope_kernel<bf16><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((bf16*)qkv, pos, cs, hq, hkv, hd, (bf16*)kcache,
-                                                                      (bf16*)vcache, cache_row, h0);
+                                                                      (bf16*)vcache, cache_row);
     else
         rope_kernel<float><<<dim3((unsigned)rows), ROW_THREADS, 0, s>>>((float*)qkv, pos, cs, hq, hkv, hd, (float*)kcache,
-                                                                       (float*)vcache, cache_row, h0);
+                                                                       (float*)vcache, cache_row);
 }
 
 // ---------------------------------------------------------------- V transpose for the matrix-core attention
