@@ -240,6 +240,15 @@ def main():
         "commit_kind": "prefill" if args.no_decode else "prefill(prompt)+decode",
         "merkle_commit": merkle,
     }
+    if not args.no_decode:
+        # the inferencer's side: every decode step streams all weights once (the embedding table is only gathered from)
+        steps_dec = max(t - pl for t, pl in zip(wl.lengths, wl.prompt_lens))
+        w_bytes = (m.n_params() - m.vocab * m.d_model) * 2
+        ms_dec = t_commit * 1e3 / max(steps_dec, 1)
+        out["decode_commit"] = {"steps": int(steps_dec), "ms_per_step_incl_prompt_prefill": round(ms_dec, 3),
+                                 "weight_bytes_per_step": int(w_bytes), "bound": "hbm",
+                                 "achieved_GBps": round(w_bytes / (ms_dec * 1e-3) / 1e9, 1), "peak_GBps": PEAK_HBM_GBS,
+                                 "frac": round(w_bytes / (ms_dec * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
 
     # ---- CPU baseline: the oracle, untuned, on a bounded sample of the same workload
     if not args.no_cpu_baseline:
