@@ -138,7 +138,8 @@ __global__ __launch_bounds__(FA_THREADS, 1) void attn_mfma_kernel(const bf16* __
     auto issue_piece = [&](int tile, int piece, const u32x4& k_rsrc, const u32x4& v_rsrc) {
         const uint32_t dst = ring_lds + (tile & (FA_SLOTS - 1)) * SLOT + (piece < NI_K ? piece * 4096 : K_BYTES + (piece - NI_K) * 4096);
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
-                     :: "v"(piece < NI_K ? k_lane[piece] : v_lane[piece - NI_K]), "s"(piece < NI_K ? k_rsrc : v_rsrc), "s"(dst));
+                     :: "v"(piece < NI_K ? k_lane[piece] : v_lane[piece - NI_K]), "s"(piece < NI_K ? k_rsrc : v_rsrc), "s"(dst)
+                     : "m0");                                 // the statement sets M0: the compiler must not keep a value there
     };
     auto issue_tile = [&](int tile) {
         u32x4 k_rsrc, v_rsrc;
