@@ -71,8 +71,9 @@ def check(asm_path: str, kernel_prefix: str = "_ZN2vl16attn_mfma_kernel") -> lis
                         problems.append(f"{name}: line {start + no2}: {mn2} {ops2[0]} writes an operand of the hand-issued "
                                         f"{mn} at line {start + no}, fewer than {OPERAND_GAP} instructions before it")
                 for no2, mn2, ops2, asm2 in ins[k + 1:k + 1 + RESULT_GAP]:
-                    if mn2.startswith("v_") and not mn2.startswith("v_mfma") and len(ops2) > 1 and (_regs(",".join(ops2[1:])) & writes):
-                        problems.append(f"{name}: line {start + no2}: {mn2} reads the result of the hand-issued {mn} at line "
+                    # reading the result, or overwriting it, before the matrix instruction has delivered it
+                    if mn2.startswith("v_") and not mn2.startswith("v_mfma") and ops2 and (_regs(",".join(ops2)) & writes):
+                        problems.append(f"{name}: line {start + no2}: {mn2} touches the result of the hand-issued {mn} at line "
                                         f"{start + no} too early")
             start = None
     return problems

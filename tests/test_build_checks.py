@@ -48,6 +48,13 @@ def test_early_read_of_a_result_is_flagged_and_compiler_issued_mfma_is_not_check
         \tv_max_f32_e32 v50, v5, v50
         """)
     assert len(check_mfma_asm.check(bad)) == 1
+    overwritten = _write(tmp_path, """\
+        \t;;#ASMSTART
+        \tv_mfma_f32_32x32x16_bf16 v[2:17], v[34:37], a[0:3], 0
+        \t;;#ASMEND
+        \tv_mov_b32_e32 v9, 0xff800000
+        """)
+    assert len(check_mfma_asm.check(overwritten)) == 1
     fine = _write(tmp_path, """\
         \tv_accvgpr_write_b32 a0, v90
         \tv_mfma_f32_32x32x16_bf16 a[4:19], v[34:37], a[0:3], a[4:19]
